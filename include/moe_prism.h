@@ -1,0 +1,188 @@
+/*
+ * moe_prism.h - C ABI of the MI355X (gfx950) routed-expert forward of an MoE FFN
+ * layer whose experts are split into sub-experts and whose top-k varies per token.
+ *
+ * Method: MoE-Prism (arXiv 2510.19366).  N experts are each cut into S
+ * sub-experts along the SwiGLU intermediate dimension (Sec. 3.2.1, Eq. 1-3); one
+ * linear gate scores all E = N*S sub-experts and a layer-wide top-k is taken
+ * (Sec. 3.2.2, expanded linear gate); the budget k belongs to a request and each
+ * of its tokens inherits it (Sec. 3.3.1).  Unlike the batch-maximum execution
+ * of Sec. 3.3.1 / 3.4.2, this library resolves k per token on the device, so the
+ * work is sum_t k_t token-sub-expert pairs (Sec. 2.1) and not T * max k.
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller unless the
+ *     argument says "host".  The library never allocates, frees or synchronises
+ *     (except moe_prism_status and moe_prism_timing_read, which say so).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     kernels of a call are enqueued on it, in order.
+ *   - `ws` is a caller-owned device workspace of at least
+ *     moe_prism_workspace_bytes() bytes, 256-byte aligned.  Its first bytes hold
+ *     a status word and counters written by the kernels; the rest is scratch.
+ *     Calls that share a workspace must be ordered on one stream.
+ *   - Return value: MOE_PRISM_OK or a negative error.  Errors found on the host
+ *     are returned before anything is launched.  Conditions visible only on the
+ *     device (a budget outside [0, k_max]) are clamped and flagged in the status
+ *     word (moe_prism_status).
+ *   - Layouts are row-major, innermost index last.  Activations and weights are
+ *     fp32 (dtype 0) or bf16 bit patterns (dtype 1); logits, routing weights and
+ *     all tables are fp32 / int32 for both.
+ *   - A token-sub-expert pair is named pair = t * k_max + j (j-th pick of token
+ *     t).  A slot is a row of the group-major pair list.  g = e * S + s is the
+ *     flat sub-expert id (expert-major).
+ */
+#ifndef MOE_PRISM_H
+#define MOE_PRISM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* exported from the shared library */
+#define MOE_PRISM_API __attribute__((visibility("default")))
+
+#define MOE_PRISM_OK 0
+#define MOE_PRISM_ERR_INVALID_ARG (-1)       /* null pointer, negative size, bad flag   */
+#define MOE_PRISM_ERR_UNSUPPORTED_SHAPE (-2) /* see moe_prism_shape                      */
+#define MOE_PRISM_ERR_WORKSPACE (-3)         /* ws_bytes < moe_prism_workspace_bytes()   */
+#define MOE_PRISM_ERR_LAUNCH (-4)            /* the HIP runtime refused a launch         */
+
+#define MOE_PRISM_F32 0
+#define MOE_PRISM_BF16 1
+
+/* status-word bits (moe_prism_status) */
+#define MOE_PRISM_STATUS_K_CLAMPED 1 /* some k_tok[t] was outside [0, k_max] and was clamped */
+
+/*
+ * Problem shape (host struct, read during the call, not retained).
+ * Supported: T >= 0; d % 64 == 0, d >= 64; inter_sub % 32 == 0; 1 <= k_max <= min(E, 1024);
+ * E = n_experts * n_sub <= 4096.  T * k_max and T * E must fit in int32.
+ */
+typedef struct {
+  int32_t T;           /* tokens in this invocation                                      */
+  int32_t d;           /* hidden size                                                    */
+  int32_t n_experts;   /* N: original experts                                            */
+  int32_t n_sub;       /* S: sub-experts per expert (the paper's N of Sec. 3.2.1)        */
+  int32_t inter_sub;   /* Is = I / S: intermediate neurons per sub-expert (C/N, Eq. 3)   */
+  int32_t k_max;       /* largest budget a token may carry, in sub-expert units          */
+  int32_t dtype;       /* MOE_PRISM_F32 or MOE_PRISM_BF16                                */
+  int32_t renormalize; /* 1: softmax over the k_t selected; 0: softmax over all E        */
+  float routed_scale;  /* multiplies every routing weight (S x the model's own factor,   */
+                       /* the "N-adjusted routed scaling" of Sec. 3.2.2)                 */
+} moe_prism_shape;
+
+/* Bytes of workspace any entry point below needs for `shape` (host only). */
+MOE_PRISM_API int moe_prism_workspace_bytes(const moe_prism_shape* shape, size_t* bytes);
+
+/*
+ * Sec. 3.3.1: every token inherits the budget of its request.
+ * req_k[R], req_off[R+1] (token ranges, req_off[0] = 0, non-decreasing) ->
+ * k_tok[req_off[R]].  R and T_total (= req_off[R], passed by the caller because
+ * req_off lives on the device) are host values.
+ */
+MOE_PRISM_API int moe_prism_expand_k(int32_t R, int32_t T_total, const int32_t* req_k, const int32_t* req_off,
+                       int32_t* k_tok, void* stream);
+
+/*
+ * Route (Sec. 3.2.2, expanded linear gate).
+ *   logits[t,g] = sum_j x[t,j] * w_router[g,j] (+ router_bias[g]), computed as one
+ *   binary32 fused-multiply-add chain per logit, j ascending, then one binary32 add
+ *   of the bias: the routing decision is reproducible bit for bit.
+ *   topk_ids[t, 0..k_t-1] = sub-experts with the k_t largest logits, ordered by
+ *   logit descending, equal logits by id ascending; entries j >= k_t are -1.
+ *   topk_w[t,j] = routed_scale * softmax weight of pick j (over the picks if
+ *   renormalize, else over all E); entries j >= k_t are 0.
+ * x [T,d], w_router [E,d] in shape->dtype; router_bias [E] fp32 or NULL;
+ * k_tok [T]; topk_ids, topk_w [T,k_max]; logits_out [T,E] fp32 or NULL (then the
+ * logits live in ws).  NaN logits are not supported.
+ */
+MOE_PRISM_API int moe_prism_route(const moe_prism_shape* shape, const void* x, const void* w_router,
+                    const float* router_bias, const int32_t* k_tok, int32_t* topk_ids,
+                    float* topk_w, float* logits_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dispatch: the pairs (Sec. 2.1) grouped by sub-expert, without a sort.
+ *   group_count[g]   = number of pairs routed to g
+ *   group_offset[g]  = exclusive prefix; group_offset[E] = P = number of pairs
+ *   sorted_pair[p]   = pair in slot p; group-major, token-ascending inside a group
+ *                      (unique, since a token picks a sub-expert at most once);
+ *                      -1 for p >= P
+ *   slot_of_pair[q]  = slot of pair q, -1 if topk_ids[q] < 0
+ * topk_ids [T,k_max] (ids in [-1, E)); group_count [E]; group_offset [E+1];
+ * sorted_pair, slot_of_pair [T*k_max].
+ */
+MOE_PRISM_API int moe_prism_dispatch(const moe_prism_shape* shape, const int32_t* topk_ids, int32_t* group_count,
+                       int32_t* group_offset, int32_t* sorted_pair, int32_t* slot_of_pair,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Grouped SwiGLU FFN over the ragged groups (Sec. 3.2.1, Eq. 1-3 restricted to
+ * one sub-expert's neurons).  For slot p of group g holding token t:
+ *   h[c]   = SiLU(x[t,:] . Wg[g,c,:]) * (x[t,:] . Wu[g,c,:]),   c < Is
+ *   y[p,q] = sum_c h[c] * Wd[g,q,c]
+ * w_gate_up [E, 2*Is, d]: rows 0..Is-1 are the gate rows, Is..2Is-1 the up rows of
+ * sub-expert g; w_down [E, d, Is].  y [T*k_max, d] in shape->dtype, rows >= P are
+ * not written.  bf16: fp32 accumulation, h rounded to bf16 once, y rounded once.
+ */
+MOE_PRISM_API int moe_prism_grouped_ffn(const moe_prism_shape* shape, const void* x, const void* w_gate_up,
+                          const void* w_down, const int32_t* group_offset,
+                          const int32_t* sorted_pair, void* y, void* ws, size_t ws_bytes,
+                          void* stream);
+
+/*
+ * Combine (Sec. 3.2.2, gate-weighted sum of the selected sub-expert outputs):
+ *   out[t,:] = sum_{j < k_t} topk_w[t,j] * y[slot_of_pair[t*k_max+j], :]
+ * j ascending, fp32 accumulation, one rounding to shape->dtype; k_t = 0 gives a
+ * zero row.  No atomics: the result is bitwise reproducible.
+ */
+MOE_PRISM_API int moe_prism_combine(const moe_prism_shape* shape, const void* y, const int32_t* slot_of_pair,
+                      const float* topk_w, const int32_t* k_tok, void* out, void* stream);
+
+/*
+ * The whole path route -> dispatch -> grouped FFN -> combine on one stream with
+ * no host synchronisation; all intermediates live in ws.  out [T,d].
+ */
+MOE_PRISM_API int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_router,
+                    const float* router_bias, const int32_t* k_tok, const void* w_gate_up,
+                    const void* w_down, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Where moe_prism_layer keeps its intermediates inside ws (host only): byte
+ * offsets of topk_ids, topk_w, group_count, group_offset, sorted_pair,
+ * slot_of_pair, y, logits, in that order, into offsets[8].
+ */
+MOE_PRISM_API int moe_prism_layer_offsets(const moe_prism_shape* shape, size_t* offsets);
+
+/* Debug: synchronises `stream`, copies the status word to *host_flags and the
+ * number of pairs of the last dispatch to *host_pairs (either may be NULL). */
+MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t* host_pairs, void* stream);
+
+/*
+ * Per-kernel timing with HIP events recorded on the caller's stream.  While
+ * enabled, every entry point brackets each kernel it launches with events.
+ * moe_prism_timing_read synchronises on the recorded events, adds the elapsed
+ * milliseconds of each kernel since the last reset into ms[MOE_PRISM_N_KERNELS]
+ * (host), the launch counts into calls[...] (host), and resets.
+ */
+#define MOE_PRISM_K_LOGITS 0
+#define MOE_PRISM_K_TOPK 1
+#define MOE_PRISM_K_DISPATCH_COUNT 2
+#define MOE_PRISM_K_DISPATCH_SCAN 3
+#define MOE_PRISM_K_DISPATCH_PLACE 4
+#define MOE_PRISM_K_FFN_TILES 5
+#define MOE_PRISM_K_FFN_GATE_UP 6
+#define MOE_PRISM_K_FFN_DOWN 7
+#define MOE_PRISM_K_COMBINE 8
+#define MOE_PRISM_N_KERNELS 9
+MOE_PRISM_API int moe_prism_timing_enable(int on);
+MOE_PRISM_API int moe_prism_timing_read(float* ms, int32_t* calls);
+
+MOE_PRISM_API const char* moe_prism_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_PRISM_H */

@@ -1,0 +1,351 @@
+// C ABI of the library (see include/moe_prism.h): argument checks, workspace
+// layout, per-kernel event timing, and the stage / layer entry points.  All
+// arithmetic is in the kernel files.
+#include "../../include/moe_prism.h"
+
+#include <mutex>
+#include <vector>
+
+#include "kernels.h"
+
+namespace mp {
+
+int num_cus() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cached = prop.multiProcessorCount;
+    if (cached <= 0) cached = 256;
+  }
+  return cached;
+}
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t hdr, logits, chunk_cnt, tiles, h, ids, w, cnt, off, sorted_pair, slot_of_pair, y, total;
+  int max_mtiles, n_chunks;
+};
+
+static int check_shape(const moe_prism_shape* s) {
+  if (s == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  if (s->T < 0 || s->d <= 0 || s->n_experts <= 0 || s->n_sub <= 0 || s->inter_sub <= 0 ||
+      s->k_max <= 0)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (s->dtype != MOE_PRISM_F32 && s->dtype != MOE_PRISM_BF16) return MOE_PRISM_ERR_INVALID_ARG;
+  if (s->renormalize != 0 && s->renormalize != 1) return MOE_PRISM_ERR_INVALID_ARG;
+  long E = (long)s->n_experts * s->n_sub;
+  if (s->d % 64 != 0 || s->inter_sub % 32 != 0) return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  if (E > 4096 || s->k_max > E || s->k_max > 1024) return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  if ((long)s->T * s->k_max >= (1L << 31) || (long)s->T * E >= (1L << 31))
+    return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  if ((long)s->T * s->k_max * s->inter_sub >= (1L << 40)) return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  return MOE_PRISM_OK;
+}
+
+static Layout layout_of(const moe_prism_shape* s) {
+  Layout L;
+  const size_t T = (size_t)s->T, E = (size_t)s->n_experts * s->n_sub, km = (size_t)s->k_max;
+  const size_t el = s->dtype == MOE_PRISM_F32 ? 4 : 2;
+  const size_t rows = T * km;
+  L.n_chunks = cdiv((long)T, 64L * dispatch_chunk_words((int)E));
+  L.max_mtiles = (int)(rows / FFN_BM + E);
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o += align256(bytes);
+    return at;
+  };
+  L.hdr = take(HDR_WORDS * 4);
+  L.logits = take(T * E * 4);
+  L.chunk_cnt = take((size_t)L.n_chunks * E * 4);
+  L.tiles = take((size_t)L.max_mtiles * sizeof(MTile));
+  L.h = take(rows * s->inter_sub * el);
+  L.ids = take(rows * 4);
+  L.w = take(rows * 4);
+  L.cnt = take(E * 4);
+  L.off = take((E + 1) * 4);
+  L.sorted_pair = take(rows * 4);
+  L.slot_of_pair = take(rows * 4);
+  L.y = take(rows * s->d * el);
+  L.total = o;
+  return L;
+}
+
+// ------------------------------------------------------------ event timing
+struct Rec {
+  int kernel;
+  hipEvent_t a, b;
+};
+static std::mutex g_mu;
+static bool g_timing = false;
+static std::vector<Rec> g_recs;
+static std::vector<hipEvent_t> g_pool;
+
+static hipEvent_t get_event() {
+  if (!g_pool.empty()) {
+    hipEvent_t e = g_pool.back();
+    g_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+struct Timed {  // brackets one kernel launch with events when timing is on
+  hipStream_t s;
+  Rec r{};
+  bool on = false;
+  Timed(int kernel, hipStream_t st) : s(st) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (!g_timing) return;
+    on = true;
+    r.kernel = kernel;
+    r.a = get_event();
+    r.b = get_event();
+    (void)hipEventRecord(r.a, s);
+  }
+  ~Timed() {
+    if (!on) return;
+    (void)hipEventRecord(r.b, s);
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_recs.push_back(r);
+  }
+};
+
+#define MP_LAUNCH(KERNEL_ID, CALL)                          \
+  do {                                                      \
+    hipError_t e_;                                          \
+    {                                                       \
+      mp::Timed timed_(KERNEL_ID, st);                      \
+      e_ = (CALL);                                          \
+    }                                                       \
+    if (e_ != hipSuccess) return MOE_PRISM_ERR_LAUNCH;      \
+  } while (0)
+
+// ------------------------------------------------------------ stages on a layout
+static int do_route(const moe_prism_shape* s, const Layout& L, const void* x, const void* w_router,
+                    const float* bias, const int32_t* k_tok, int32_t* ids, float* w, float* logits,
+                    char* ws, hipStream_t st) {
+  const int E = s->n_experts * s->n_sub;
+  int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
+  MP_LAUNCH(MOE_PRISM_K_LOGITS,
+            launch_logits(s->dtype, x, w_router, bias, logits, hdr, s->T, s->d, E, st));
+  MP_LAUNCH(MOE_PRISM_K_TOPK, launch_topk(logits, k_tok, ids, w, hdr, s->T, E, s->k_max,
+                                          s->renormalize, s->routed_scale, st));
+  return MOE_PRISM_OK;
+}
+
+static int do_dispatch(const moe_prism_shape* s, const Layout& L, const int32_t* ids, int32_t* cnt,
+                       int32_t* off, int32_t* sorted_pair, int32_t* slot_of_pair, char* ws,
+                       hipStream_t st) {
+  const int E = s->n_experts * s->n_sub;
+  int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
+  int32_t* chunk = reinterpret_cast<int32_t*>(ws + L.chunk_cnt);
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_COUNT, launch_dispatch_count(ids, chunk, s->T, E, s->k_max, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, cnt, off, hdr, s->T, E, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_PLACE,
+            launch_dispatch_place(ids, chunk, off, sorted_pair, slot_of_pair, s->T, E, s->k_max, st));
+  return MOE_PRISM_OK;
+}
+
+static int do_ffn(const moe_prism_shape* s, const Layout& L, const void* x, const void* w_gu,
+                  const void* w_dn, const int32_t* off, const int32_t* sorted_pair, void* y,
+                  char* ws, hipStream_t st) {
+  const int E = s->n_experts * s->n_sub;
+  int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
+  MTile* tiles = reinterpret_cast<MTile*>(ws + L.tiles);
+  void* h = ws + L.h;
+  MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(off, tiles, hdr, E, L.max_mtiles, s->T * s->k_max, st));
+  if (s->T == 0) return MOE_PRISM_OK;
+  MP_LAUNCH(MOE_PRISM_K_FFN_GATE_UP,
+            launch_ffn_gate_up(s->dtype, x, w_gu, sorted_pair, tiles, hdr, h, s->T, s->d, s->inter_sub,
+                               s->k_max, L.max_mtiles, st));
+  MP_LAUNCH(MOE_PRISM_K_FFN_DOWN, launch_ffn_down(s->dtype, h, w_dn, tiles, hdr, y, s->d,
+                                                  s->inter_sub, L.max_mtiles, st));
+  return MOE_PRISM_OK;
+}
+
+}  // namespace mp
+
+using namespace mp;
+
+#define MP_CHECK_SHAPE(s)            \
+  do {                               \
+    int rc_ = check_shape(s);        \
+    if (rc_ != MOE_PRISM_OK) return rc_; \
+  } while (0)
+
+#define MP_CHECK_WS(s, L, ws, ws_bytes)                                          \
+  Layout L = layout_of(s);                                                       \
+  do {                                                                           \
+    if ((ws) == nullptr || ((uintptr_t)(ws) & 255) != 0) return MOE_PRISM_ERR_INVALID_ARG; \
+    if ((ws_bytes) < L.total) return MOE_PRISM_ERR_WORKSPACE;                    \
+  } while (0)
+
+extern "C" {
+
+int moe_prism_workspace_bytes(const moe_prism_shape* shape, size_t* bytes) {
+  if (bytes == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_SHAPE(shape);
+  *bytes = layout_of(shape).total;
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_layer_offsets(const moe_prism_shape* shape, size_t* offsets) {
+  if (offsets == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_SHAPE(shape);
+  Layout L = layout_of(shape);
+  size_t v[8] = {L.ids, L.w, L.cnt, L.off, L.sorted_pair, L.slot_of_pair, L.y, L.logits};
+  for (int i = 0; i < 8; ++i) offsets[i] = v[i];
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_expand_k(int32_t R, int32_t T_total, const int32_t* req_k, const int32_t* req_off,
+                       int32_t* k_tok, void* stream) {
+  if (R < 0 || T_total < 0) return MOE_PRISM_ERR_INVALID_ARG;
+  if (R == 0 || T_total == 0) return MOE_PRISM_OK;
+  if (req_k == nullptr || req_off == nullptr || k_tok == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  if (launch_expand_k(R, T_total, req_k, req_off, k_tok, st) != hipSuccess)
+    return MOE_PRISM_ERR_LAUNCH;
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_route(const moe_prism_shape* shape, const void* x, const void* w_router,
+                    const float* router_bias, const int32_t* k_tok, int32_t* topk_ids,
+                    float* topk_w, float* logits_out, void* ws, size_t ws_bytes, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (w_router == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || topk_ids == nullptr || topk_w == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  char* w8 = static_cast<char*>(ws);
+  float* logits = logits_out ? logits_out : reinterpret_cast<float*>(w8 + L.logits);
+  return do_route(shape, L, x, w_router, router_bias, k_tok, topk_ids, topk_w, logits, w8,
+                  (hipStream_t)stream);
+}
+
+int moe_prism_dispatch(const moe_prism_shape* shape, const int32_t* topk_ids, int32_t* group_count,
+                       int32_t* group_offset, int32_t* sorted_pair, int32_t* slot_of_pair,
+                       void* ws, size_t ws_bytes, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (group_count == nullptr || group_offset == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (topk_ids == nullptr || sorted_pair == nullptr || slot_of_pair == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  return do_dispatch(shape, L, topk_ids, group_count, group_offset, sorted_pair, slot_of_pair,
+                     static_cast<char*>(ws), (hipStream_t)stream);
+}
+
+int moe_prism_grouped_ffn(const moe_prism_shape* shape, const void* x, const void* w_gate_up,
+                          const void* w_down, const int32_t* group_offset,
+                          const int32_t* sorted_pair, void* y, void* ws, size_t ws_bytes,
+                          void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (w_gate_up == nullptr || w_down == nullptr || group_offset == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || sorted_pair == nullptr || y == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  return do_ffn(shape, L, x, w_gate_up, w_down, group_offset, sorted_pair, y,
+                static_cast<char*>(ws), (hipStream_t)stream);
+}
+
+int moe_prism_combine(const moe_prism_shape* shape, const void* y, const int32_t* slot_of_pair,
+                      const float* topk_w, const int32_t* k_tok, void* out, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (shape->T == 0) return MOE_PRISM_OK;
+  if (y == nullptr || slot_of_pair == nullptr || topk_w == nullptr || k_tok == nullptr ||
+      out == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  MP_LAUNCH(MOE_PRISM_K_COMBINE, launch_combine(shape->dtype, y, slot_of_pair, topk_w, k_tok, out,
+                                                shape->T, shape->d, shape->k_max, st));
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_router,
+                    const float* router_bias, const int32_t* k_tok, const void* w_gate_up,
+                    const void* w_down, void* out, void* ws, size_t ws_bytes, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (w_router == nullptr || w_gate_up == nullptr || w_down == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || out == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  char* w8 = static_cast<char*>(ws);
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* ids = reinterpret_cast<int32_t*>(w8 + L.ids);
+  float* w = reinterpret_cast<float*>(w8 + L.w);
+  int32_t* cnt = reinterpret_cast<int32_t*>(w8 + L.cnt);
+  int32_t* off = reinterpret_cast<int32_t*>(w8 + L.off);
+  int32_t* sp = reinterpret_cast<int32_t*>(w8 + L.sorted_pair);
+  int32_t* sl = reinterpret_cast<int32_t*>(w8 + L.slot_of_pair);
+  void* y = w8 + L.y;
+  int rc = do_route(shape, L, x, w_router, router_bias, k_tok, ids, w,
+                    reinterpret_cast<float*>(w8 + L.logits), w8, st);
+  if (rc) return rc;
+  rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st);
+  if (rc) return rc;
+  rc = do_ffn(shape, L, x, w_gate_up, w_down, off, sp, y, w8, st);
+  if (rc) return rc;
+  if (shape->T == 0) return MOE_PRISM_OK;
+  MP_LAUNCH(MOE_PRISM_K_COMBINE, launch_combine(shape->dtype, y, sl, w, k_tok, out, shape->T,
+                                                shape->d, shape->k_max, st));
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_status(const void* ws, int32_t* host_flags, int32_t* host_pairs, void* stream) {
+  if (ws == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  int32_t hdr[2] = {0, 0};
+  hipStream_t st = (hipStream_t)stream;
+  if (hipMemcpyAsync(hdr, ws, sizeof(hdr), hipMemcpyDeviceToHost, st) != hipSuccess)
+    return MOE_PRISM_ERR_LAUNCH;
+  if (hipStreamSynchronize(st) != hipSuccess) return MOE_PRISM_ERR_LAUNCH;
+  if (host_flags) *host_flags = hdr[HDR_FLAGS];
+  if (host_pairs) *host_pairs = hdr[HDR_PAIRS];
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_timing_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  g_timing = on != 0;
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_timing_read(float* ms, int32_t* calls) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  for (int i = 0; i < MOE_PRISM_N_KERNELS; ++i) {
+    if (ms) ms[i] = 0.0f;
+    if (calls) calls[i] = 0;
+  }
+  int rc = MOE_PRISM_OK;
+  for (const Rec& r : g_recs) {
+    float t = 0.0f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess)
+      rc = MOE_PRISM_ERR_LAUNCH;
+    if (ms) ms[r.kernel] += t;
+    if (calls) calls[r.kernel] += 1;
+    g_pool.push_back(r.a);
+    g_pool.push_back(r.b);
+  }
+  g_recs.clear();
+  return rc;
+}
+
+const char* moe_prism_strerror(int code) {
+  switch (code) {
+    case MOE_PRISM_OK: return "ok";
+    case MOE_PRISM_ERR_INVALID_ARG: return "invalid argument (null pointer, negative size, bad flag, unaligned workspace)";
+    case MOE_PRISM_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (need d % 64 == 0, inter_sub % 32 == 0, k_max <= min(E, 1024), E <= 4096, int32 index range)";
+    case MOE_PRISM_ERR_WORKSPACE: return "workspace smaller than moe_prism_workspace_bytes()";
+    case MOE_PRISM_ERR_LAUNCH: return "HIP runtime error while enqueuing";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

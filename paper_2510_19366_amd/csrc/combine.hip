@@ -1,0 +1,94 @@
+// Combine stage (Sec. 3.2.2): out[t,:] = sum_{j<k_t} w[t,j] * y[slot(t,j),:].
+// One workgroup per token, 16-byte column vectors per thread, picks visited in
+// ascending j with fp32 accumulation and a single final rounding.  No atomics:
+// every output element has exactly one writer, so the result is reproducible.
+#include "kernels.h"
+
+namespace mp {
+
+template <int DT> struct Vec;  // 16 bytes of a row
+template <> struct Vec<0> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void load(const void* base, size_t elem, float (&v)[8]) {
+    float4 a = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  }
+  static __device__ __forceinline__ void store(void* base, size_t elem, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(static_cast<float*>(base) + elem) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct Vec<1> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void load(const void* base, size_t elem, float (&v)[8]) {
+    uint4 a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem);
+    uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(void* base, size_t elem, const float (&v)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(static_cast<uint16_t*>(base) + elem) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y,
+                                                      const int32_t* __restrict__ slot_of_pair,
+                                                      const float* __restrict__ w,
+                                                      const int32_t* __restrict__ k_tok,
+                                                      void* __restrict__ out, int d, int k_max,
+                                                      int n_rows) {
+  constexpr int N = Vec<DT>::N;
+  const int t = blockIdx.x;
+  int kt = k_tok[t];
+  kt = kt < 0 ? 0 : (kt > k_max ? k_max : kt);
+  const int32_t* slots = slot_of_pair + (size_t)t * k_max;
+  const float* wt = w + (size_t)t * k_max;
+  for (int col = threadIdx.x * N; col < d; col += 256 * N) {
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int j = 0;
+    for (; j + 4 <= kt; j += 4) {  // four rows in flight, still added in ascending j
+      float v[4][8];
+      float wj[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int sl = slots[j + u];
+        bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing
+        wj[u] = ok ? wt[j + u] : 0.0f;
+        Vec<DT>::load(y, (size_t)(ok ? sl : 0) * d + col, v[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] = fmaf(wj[u], v[u][e], acc[e]);
+    }
+    for (; j < kt; ++j) {
+      float v[8];
+      int sl = slots[j];
+      bool ok = sl >= 0 && sl < n_rows;
+      float wj = ok ? wt[j] : 0.0f;
+      Vec<DT>::load(y, (size_t)(ok ? sl : 0) * d + col, v);
+#pragma unroll
+      for (int e = 0; e < N; ++e) acc[e] = fmaf(wj, v[e], acc[e]);
+    }
+    Vec<DT>::store(out, (size_t)t * d + col, acc);
+  }
+}
+
+hipError_t launch_combine(int dtype, const void* y, const int32_t* slot_of_pair, const float* w,
+                          const int32_t* k_tok, void* out, int T, int d, int k_max, hipStream_t s) {
+  if (T == 0) return hipSuccess;
+  if (dtype == 0)
+    combine_kernel<0><<<T, 256, 0, s>>>(y, slot_of_pair, w, k_tok, out, d, k_max, T * k_max);
+  else
+    combine_kernel<1><<<T, 256, 0, s>>>(y, slot_of_pair, w, k_tok, out, d, k_max, T * k_max);
+  return hipGetLastError();
+}
+
+}  // namespace mp

@@ -1,0 +1,65 @@
+// Internal launcher interface between the C ABI (api.hip) and the kernel files.
+// gfx950 only.  Every launcher enqueues on `s` and returns hipGetLastError().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mp {
+
+// Workspace header: int32 words at the start of ws.
+enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_WORDS = 64 };
+
+constexpr int FFN_BM = 128;  // rows of one m-tile of the grouped GEMMs
+
+struct MTile {       // one m-tile of a group: rows [row0, row0 + rows) of the slot list
+  int32_t g, row0, rows, pad;
+};
+
+inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+hipError_t launch_expand_k(int R, int T, const int32_t* req_k, const int32_t* req_off,
+                           int32_t* k_tok, hipStream_t s);
+
+hipError_t launch_logits(int dtype, const void* x, const void* w, const float* bias, float* logits,
+                         int32_t* hdr, int T, int d, int E, hipStream_t s);
+hipError_t launch_topk(const float* logits, const int32_t* k_tok, int32_t* ids, float* w,
+                       int32_t* hdr, int T, int E, int k_max, int renorm, float scale,
+                       hipStream_t s);
+
+// dispatch: chunk_cnt is [n_chunks, E] scratch
+int dispatch_chunk_words(int E);                 // 64-token words per chunk
+hipError_t launch_dispatch_count(const int32_t* ids, int32_t* chunk_cnt, int T, int E, int k_max,
+                                 hipStream_t s);
+hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int32_t* off, int32_t* hdr, int T,
+                                int E, hipStream_t s);
+hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* off,
+                                 int32_t* sorted_pair, int32_t* slot_of_pair, int T, int E,
+                                 int k_max, hipStream_t s);
+
+// grouped FFN
+hipError_t launch_ffn_tiles(const int32_t* off, MTile* tiles, int32_t* hdr, int E, int max_tiles,
+                            int n_rows, hipStream_t s);
+hipError_t launch_ffn_gate_up(int dtype, const void* x, const void* w_gu, const int32_t* sorted_pair,
+                              const MTile* tiles, const int32_t* hdr, void* h, int T, int d, int Is,
+                              int k_max, int max_mtiles, hipStream_t s);
+hipError_t launch_ffn_down(int dtype, const void* h, const void* w_dn, const MTile* tiles,
+                           const int32_t* hdr, void* y, int d, int Is, int max_mtiles,
+                           hipStream_t s);
+
+hipError_t launch_combine(int dtype, const void* y, const int32_t* slot_of_pair, const float* w,
+                          const int32_t* k_tok, void* out, int T, int d, int k_max, hipStream_t s);
+
+int num_cus();  // compute units of the current device (cached)
+
+// bf16 helpers (bit patterns in uint16_t)
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+}  // namespace mp

@@ -1,0 +1,317 @@
+// Route stage (Sec. 3.2.2, expanded linear gate): router logits with a fixed
+// summation order, then per-token top-k_t and softmax weights.
+#include "kernels.h"
+
+namespace mp {
+
+// ---------------------------------------------------------------- expand_k
+// Sec. 3.3.1: a token inherits its request's budget.
+__global__ void expand_k_kernel(int R, const int32_t* __restrict__ req_k,
+                                const int32_t* __restrict__ req_off, int32_t* __restrict__ k_tok) {
+  int r = blockIdx.x;
+  if (r >= R) return;
+  int lo = req_off[r], hi = req_off[r + 1], k = req_k[r];
+  for (int t = lo + threadIdx.x; t < hi; t += blockDim.x) k_tok[t] = k;
+}
+
+hipError_t launch_expand_k(int R, int T, const int32_t* req_k, const int32_t* req_off,
+                           int32_t* k_tok, hipStream_t s) {
+  (void)T;
+  if (R > 0) expand_k_kernel<<<R, 256, 0, s>>>(R, req_k, req_off, k_tok);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- logits
+// Each thread owns a TM x TN block of logits and walks the hidden index in
+// ascending order with one fused multiply-add per step, so every logit is the
+// same binary32 chain regardless of tiling.  x and w_router tiles are widened to
+// fp32 (exact for bf16) and staged through LDS, k-major, so that a thread reads
+// its operands as float4.
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int per16 = 4; };
+template <> struct Elem<uint16_t> { static constexpr int per16 = 8; };
+
+template <typename InT>
+__device__ __forceinline__ void load8(const InT* p, float (&v)[8]);
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
+  float4 a = *reinterpret_cast<const float4*>(p);
+  float4 b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+  v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float (&v)[8]) {
+  uint4 a = *reinterpret_cast<const uint4*>(p);
+  uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float(w[i] << 16);
+    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+
+constexpr int LG_BK = 32;
+
+template <typename InT, int BM, int BN, int TM, int TN>
+__global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
+                                                     const InT* __restrict__ w,
+                                                     const float* __restrict__ bias,
+                                                     float* __restrict__ logits,
+                                                     int32_t* __restrict__ hdr, int T, int d,
+                                                     int E) {
+  static_assert((BM / TM) * (BN / TN) == 256, "256 threads");
+  static_assert(TM % 4 == 0 && TN % 4 == 0, "float4 operands");
+  constexpr int LDA = BM + 4, LDB = BN + 4;
+  constexpr int A8 = BM * LG_BK / 8 / 256;  // 8-element loads per thread
+  constexpr int B8 = (BN * LG_BK / 8 + 255) / 256;
+  __shared__ float As[LG_BK * LDA];
+  __shared__ float Bs[LG_BK * LDB];
+
+  const int tid = threadIdx.x;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) hdr[HDR_FLAGS] = 0;
+  const int tx = tid % (BN / TN), ty = tid / (BN / TN);
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+  float acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
+
+  float pa[A8][8], pb[B8][8];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < A8; ++i) {
+      int c = tid + i * 256;  // chunk id: row = c / 4, k-chunk = c % 4
+      int row = min(m0 + c / (LG_BK / 8), T - 1);
+      load8<InT>(x + (size_t)row * d + k0 + (c % (LG_BK / 8)) * 8, pa[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < B8; ++i) {
+      int c = tid + i * 256;
+      if (c < BN * LG_BK / 8) {
+        int row = min(n0 + c / (LG_BK / 8), E - 1);
+        load8<InT>(w + (size_t)row * d + k0 + (c % (LG_BK / 8)) * 8, pb[i]);
+      }
+    }
+  };
+  auto sstore = [&]() {
+#pragma unroll
+    for (int i = 0; i < A8; ++i) {
+      int c = tid + i * 256;
+      int r = c / (LG_BK / 8), kc = (c % (LG_BK / 8)) * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) As[(kc + e) * LDA + r] = pa[i][e];
+    }
+#pragma unroll
+    for (int i = 0; i < B8; ++i) {
+      int c = tid + i * 256;
+      if (c < BN * LG_BK / 8) {
+        int r = c / (LG_BK / 8), kc = (c % (LG_BK / 8)) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Bs[(kc + e) * LDB + r] = pb[i][e];
+      }
+    }
+  };
+
+  gload(0);
+  for (int k0 = 0; k0 < d; k0 += LG_BK) {
+    __syncthreads();
+    sstore();
+    __syncthreads();
+    if (k0 + LG_BK < d) gload(k0 + LG_BK);
+#pragma unroll
+    for (int kk = 0; kk < LG_BK; ++kk) {
+      float a[TM], b[TN];
+#pragma unroll
+      for (int h = 0; h < TM / 4; ++h) {
+        float4 v = *reinterpret_cast<const float4*>(&As[kk * LDA + h * (BM * 4 / TM) + ty * 4]);
+        a[4 * h] = v.x; a[4 * h + 1] = v.y; a[4 * h + 2] = v.z; a[4 * h + 3] = v.w;
+      }
+#pragma unroll
+      for (int h = 0; h < TN / 4; ++h) {
+        float4 v = *reinterpret_cast<const float4*>(&Bs[kk * LDB + h * (BN * 4 / TN) + tx * 4]);
+        b[4 * h] = v.x; b[4 * h + 1] = v.y; b[4 * h + 2] = v.z; b[4 * h + 3] = v.w;
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    int row = m0 + (i / 4) * (BM * 4 / TM) + ty * 4 + (i % 4);
+    if (row >= T) continue;
+#pragma unroll
+    for (int h = 0; h < TN / 4; ++h) {
+      int col = n0 + h * (BN * 4 / TN) + tx * 4;
+      float v[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        v[j] = acc[i][4 * h + j];
+        if (bias != nullptr && col + j < E) v[j] = v[j] + bias[col + j];
+      }
+      if (col + 3 < E && (E % 4) == 0) {
+        *reinterpret_cast<float4*>(&logits[(size_t)row * E + col]) =
+            make_float4(v[0], v[1], v[2], v[3]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (col + j < E) logits[(size_t)row * E + col + j] = v[j];
+      }
+    }
+  }
+}
+
+__global__ void clear_flags_kernel(int32_t* hdr) { hdr[HDR_FLAGS] = 0; }
+
+hipError_t launch_logits(int dtype, const void* x, const void* w, const float* bias, float* logits,
+                         int32_t* hdr, int T, int d, int E, hipStream_t s) {
+  if (T == 0) {
+    clear_flags_kernel<<<1, 1, 0, s>>>(hdr);
+    return hipGetLastError();
+  }
+  if (E > 64) {
+    dim3 grid(cdiv(E, 128), cdiv(T, 128));
+    if (dtype == 0)
+      logits_kernel<float, 128, 128, 8, 8><<<grid, 256, 0, s>>>(
+          (const float*)x, (const float*)w, bias, logits, hdr, T, d, E);
+    else
+      logits_kernel<uint16_t, 128, 128, 8, 8><<<grid, 256, 0, s>>>(
+          (const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E);
+  } else {
+    dim3 grid(cdiv(E, 32), cdiv(T, 128));
+    if (dtype == 0)
+      logits_kernel<float, 128, 32, 4, 4><<<grid, 256, 0, s>>>(
+          (const float*)x, (const float*)w, bias, logits, hdr, T, d, E);
+    else
+      logits_kernel<uint16_t, 128, 32, 4, 4><<<grid, 256, 0, s>>>(
+          (const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- top-k_t + weights
+// One wavefront per token.  Lane l holds logits g = i*64 + l.  Pick j is the
+// wave-wide arg-max over the logits not yet taken, by (logit desc, id asc),
+// reduced with cross-lane shuffles; no sort and no global traffic besides the
+// logits row and the outputs.
+struct Best {
+  float v;
+  int g;
+};
+__device__ __forceinline__ Best better(Best a, Best b) {
+  return (b.v > a.v || (b.v == a.v && b.g < a.g)) ? b : a;
+}
+__device__ __forceinline__ Best wave_best(Best x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) {
+    Best o;
+    o.v = __shfl_xor(x.v, m, 64);
+    o.g = __shfl_xor(x.g, m, 64);
+    x = better(x, o);
+  }
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+
+constexpr int TOPK_WAVES = 4;
+
+template <int ELEMS>
+__global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
+    const float* __restrict__ logits, const int32_t* __restrict__ k_tok, int32_t* __restrict__ ids,
+    float* __restrict__ wout, int32_t* __restrict__ hdr, int T, int E, int k_max, int renorm,
+    float scale) {
+  extern __shared__ float smem[];  // per wave: k_max exponentials, then k_max ids
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int t = blockIdx.x * TOPK_WAVES + wv;
+  if (t >= T) return;
+  float* se = smem + (size_t)wv * 2 * k_max;
+  int* sid = reinterpret_cast<int*>(se + k_max);
+
+  int kt = k_tok[t];
+  if (kt < 0 || kt > k_max) {
+    if (lane == 0) atomicOr(&hdr[HDR_FLAGS], 1);
+    kt = kt < 0 ? 0 : k_max;
+  }
+
+  const float NEG_INF = -__builtin_inff();
+  float v[ELEMS];
+  const float* row = logits + (size_t)t * E;
+#pragma unroll
+  for (int i = 0; i < ELEMS; ++i) {
+    int g = i * 64 + lane;
+    v[i] = g < E ? row[g] : NEG_INF;
+  }
+  // full-softmax denominator (only needed when weights are not renormalised)
+  float mx = NEG_INF;
+#pragma unroll
+  for (int i = 0; i < ELEMS; ++i) mx = fmaxf(mx, v[i]);
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  float denom = 0.0f;
+  if (!renorm) {
+#pragma unroll
+    for (int i = 0; i < ELEMS; ++i)
+      if (i * 64 + lane < E) denom += expf(v[i] - mx);
+    denom = wave_sum(denom);
+  }
+
+  unsigned long long taken = 0ull;  // bit i: this lane's element i was picked
+  float dsel = 0.0f;
+  for (int j = 0; j < kt; ++j) {
+    Best b{NEG_INF, 0x7fffffff};
+#pragma unroll
+    for (int i = 0; i < ELEMS; ++i) {
+      int g = i * 64 + lane;
+      bool free_ = g < E && !((taken >> i) & 1ull);
+      Best c{v[i], g};
+      if (free_) b = better(b, c);  // ascending g inside a lane: strict > keeps the lower id
+    }
+    b = wave_best(b);
+    if ((b.g & 63) == lane) taken |= 1ull << (b.g >> 6);
+    float e = expf(b.v - mx);
+    dsel += e;
+    if (lane == 0) {
+      se[j] = e;
+      sid[j] = b.g;
+    }
+  }
+  if (renorm) denom = dsel;
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of lane 0 are done
+  for (int j = lane; j < k_max; j += 64) {
+    bool on = j < kt;
+    ids[(size_t)t * k_max + j] = on ? sid[j] : -1;
+    wout[(size_t)t * k_max + j] = on ? scale * se[j] / denom : 0.0f;
+  }
+}
+
+hipError_t launch_topk(const float* logits, const int32_t* k_tok, int32_t* ids, float* w,
+                       int32_t* hdr, int T, int E, int k_max, int renorm, float scale,
+                       hipStream_t s) {
+  if (T == 0) return hipSuccess;
+  dim3 grid(cdiv(T, TOPK_WAVES)), block(64 * TOPK_WAVES);
+  size_t sh = (size_t)TOPK_WAVES * 2 * k_max * sizeof(float);
+  int elems = cdiv(E, 64);
+#define MP_TOPK(N)                                                                              \
+  topk_kernel<N><<<grid, block, sh, s>>>(logits, k_tok, ids, w, hdr, T, E, k_max, renorm, scale)
+  if (elems <= 1) MP_TOPK(1);
+  else if (elems <= 2) MP_TOPK(2);
+  else if (elems <= 4) MP_TOPK(4);
+  else if (elems <= 8) MP_TOPK(8);
+  else if (elems <= 16) MP_TOPK(16);
+  else if (elems <= 32) MP_TOPK(32);
+  else MP_TOPK(64);
+#undef MP_TOPK
+  return hipGetLastError();
+}
+
+}  // namespace mp
