@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark of the routed-expert forward (route -> dispatch -> grouped FFN -> combine).
+
+One "step" is one call of moe_prism_layer over one batch of synthetic tokens that is
+already resident in HBM.  Prints ONE JSON line: whole-layer routed tokens/s, the
+roofline of the dominant kernel from HIP events recorded inside the timed region,
+per-kernel times, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured for that workload.
+TRAFFIC_BYTES = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3_fine_128x4",
+                    help="c2_mixtral_8x4 | c3_fine_128x4 | c4_decode_64x2 | c5a_s1_k8 | c5b_s4_k32")
+    ap.add_argument("--tokens", type=int, default=None, help="token count for the c5 sweep")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_19366_amd import binding as B
+    from paper_2510_19366_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = W.config(args.workload, T=args.tokens) if args.workload.startswith("c5") else W.config(args.workload)
+    dev = B.to_device(wl)
+    shape = dev["shape"]
+    ws = B.alloc_workspace(shape)
+    out = torch.empty((wl.T, wl.d), dtype=B.act_dtype(shape), device="cuda")
+
+    def step():
+        B.moe_prism_layer(shape, dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"],
+                          dev["w_gate_up"], dev["w_down"], ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.moe_prism_timing_enable(True)
+    B.moe_prism_timing_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kt = B.moe_prism_timing_read()
+    B.moe_prism_timing_enable(False)
+    flags, pairs = B.moe_prism_status(ws)
+    assert flags == 0 and pairs == wl.pairs, (flags, pairs, wl.pairs)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = wl.T / (ms_per_step * 1e-3)
+    kern_ms = {k: (v[0] / max(v[1], 1)) for k, v in kt.items()}
+    P, d, Is, E = wl.pairs, wl.d, wl.inter_sub, wl.E
+
+    # dominant kernel: the gate-up GEMM (2/3 of the FFN FLOPs); algorithmic FLOPs = 4*d*Is per pair
+    gu_flops = 4.0 * d * Is * P
+    ffn_flops = 6.0 * d * Is * P
+    gu_tflops = gu_flops / (kern_ms["ffn_gate_up"] * 1e-3) / 1e12
+    ffn_ms = kern_ms["ffn_gate_up"] + kern_ms["ffn_down"] + kern_ms["ffn_tiles"]
+    ffn_tflops = ffn_flops / (ffn_ms * 1e-3) / 1e12
+    el = 2 if wl.dtype == "bf16" else 4
+    stage_bytes = {
+        "logits": wl.T * d * el + E * d * el + wl.T * E * 4,
+        "topk": wl.T * E * 4 + 2 * wl.T * wl.k_max * 4,
+        "combine": P * d * el + wl.T * d * el + 2 * P * 4,
+        "ffn_down": P * Is * el + E * d * Is * el + P * d * el,
+    }
+    res = {
+        "metric": "routed tokens/sec (whole layer, mixed per-request k, 1 GPU); grouped-FFN MFMA util in ffn_mfma_util_pct",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "T": wl.T, "d": d, "n_experts": wl.n_experts,
+                   "n_sub": wl.n_sub, "inter_sub": Is, "k_max": wl.k_max, "pairs": P,
+                   "requests": int(len(wl.req_k)), "k_mix": "per-request"},
+        "ffn_mfma_util_pct": 100.0 * ffn_tflops / PEAK_BF16_TFLOPS,
+        "ffn_tflops": ffn_tflops,
+        "ffn_ms": ffn_ms,
+        "roofline": {"kernel": "ffn_gate_up", "bound": "mfma", "achieved": gu_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": gu_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": TRAFFIC_BYTES.get(wl.name)},
+        "kernels_ms": kern_ms,
+        "stage_gbs": {k: v / (kern_ms[k] * 1e-3) / 1e9 for k, v in stage_bytes.items()
+                      if kern_ms.get(k, 0) > 0},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        x32, wr32 = wl.x, wl.w_router
+        rng = np.random.default_rng(0)
+        n, spent, done = 4, 0.0, 0
+        perm = rng.permutation(wl.T)
+        # grow the sample until ~cpu-seconds of oracle work has been spent
+        while done < wl.T and spent < args.cpu_seconds:
+            n = min(n, wl.T - done)
+            tok = np.sort(perm[done:done + n]).astype(np.int32)
+            c0 = time.perf_counter()
+            O.layer_tokens(tok, x32, wr32, wl.router_bias, wl.k_tok, wl.w_gate_up, wl.w_down,
+                           wl.k_max, wl.renormalize, wl.routed_scale)
+            dt = time.perf_counter() - c0
+            spent += dt
+            done += n
+            rate = n / max(dt, 1e-9)
+            n = int(max(4, min(rate * (args.cpu_seconds - spent) * 0.9, 4 * n)))
+        res["cpu_baseline"] = {"value": done / spent, "unit": "tokens/s", "cores": O.n_threads(),
+                               "kind": "oracle",
+                               "sample": f"{done} of {wl.T} tokens of {wl.name} drawn at random, "
+                                         f"whole layer per token (fp64 plain C, OpenMP), {spent:.1f} s"}
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
