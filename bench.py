@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=None, help="token count for the c5 sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy 5 times (known traffic, for scaling "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -57,6 +60,14 @@ def main():
     def step():
         B.moe_prism_layer(shape, dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"],
                           dev["w_gate_up"], dev["w_down"], ws, out=out)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -9,7 +9,7 @@ namespace mp {
 // Workspace header: int32 words at the start of ws.
 enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_WORDS = 64 };
 
-constexpr int FFN_BM = 128;  // rows of one m-tile of the grouped GEMMs
+constexpr int FFN_BM = 256;  // rows of one m-tile of the grouped GEMMs
 
 struct MTile {       // one m-tile of a group: rows [row0, row0 + rows) of the slot list
   int32_t g, row0, rows, pad;
