@@ -127,6 +127,12 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
   return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
+// What every lane knows about a work item: group, first slot row, valid rows, first
+// output column (or neuron) of the n-tile.  Wave-uniform.
+struct Sc {
+  int g, row0, rows, n0;
+};
+
 // Generic persistent driver.  Op supplies the per-item state (Item), the row addresses
 // (a_row: slot rows, b_row: weight rows) and the epilogue.
 template <int BN, class Op>
@@ -172,19 +178,13 @@ __device__ __forceinline__ void run_items(const Op& op, const MTile* __restrict_
 
     for (int s = 0; s < nslab; ++s) {
       const bool last = s == nslab - 1;
-#ifndef MP_EXP_NOLOAD
       if (!last)
         pipe.gload(op, cur, (s + 1) * BK, K);
       else if (has_next)
         pipe.gload(op, nxt, 0, K);
-#endif
-#ifndef MP_EXP_NOMFMA
       pipe.compute(buf, acc, mb_on, wrow);
-#endif
       if (last) op.epilogue(cur, acc, mb_on);
-#ifndef MP_EXP_NOLOAD
       if (!last || has_next) pipe.sstore(buf ^ 1);
-#endif
       __syncthreads();
       buf ^= 1;
     }
@@ -212,9 +212,9 @@ struct GateUpOp {
   uint16_t* h;
   int T, d, Is, k_max;
 
-  struct Item {
-    int g, row0, rows, n0;  // uniform
-    int tok[A_LD];          // tokens of the slot rows this thread copies
+  static constexpr bool GATHER = true;
+  struct Item : Sc {
+    int tok[A_LD];  // tokens of the slot rows this thread copies
   };
 
   static __device__ __forceinline__ int wrow(int i) {
@@ -236,12 +236,26 @@ struct GateUpOp {
   __device__ __forceinline__ const uint16_t* a_row(const Item& it, int, int i) const {
     return x + (size_t)it.tok[i] * d;
   }
-  __device__ __forceinline__ const uint16_t* b_row(const Item& it, int br) const {
+  // DMA driver: header only; the slot list entries of the tile's rows arrive through LDS
+  __device__ __forceinline__ void setup_sc(const MTile& t, int nt, Sc& sc) const {
+    sc.g = uni(t.g);
+    sc.row0 = uni(t.row0);
+    sc.rows = uni(t.rows);
+    sc.n0 = uni(nt) * (BN / 2);
+  }
+  __device__ __forceinline__ const int32_t* idx_src(const Sc& sc, int r) const {
+    return sorted_pair + sc.row0 + min(r, sc.rows - 1);
+  }
+  __device__ __forceinline__ const uint16_t* a_src(const Sc&, int r, const int32_t* pair_lds) const {
+    const int tok = pair_lds[r] / k_max;
+    return x + (size_t)min(max(tok, 0), T - 1) * d;
+  }
+  __device__ __forceinline__ const uint16_t* b_row(const Sc& it, int br) const {
     const int blk = br >> 5, rr = br & 31;  // 32-row block of the tile, row inside it
     const int neuron = min(it.n0 + blk * 16 + (rr & 15), Is - 1);
     return w_gu + ((size_t)it.g * 2 * Is + ((rr >> 4) ? Is + neuron : neuron)) * d;
   }
-  __device__ __forceinline__ void epilogue(const Item& it, f32x16 (&acc)[Tile<BN>::NB][2],
+  __device__ __forceinline__ void epilogue(const Sc& it, f32x16 (&acc)[Tile<BN>::NB][2],
                                            int mb_on) const {
     constexpr int NB = Tile<BN>::NB;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -289,9 +303,8 @@ struct DownOp {
   uint16_t* y;
   int d, Is;
 
-  struct Item {
-    int g, row0, rows, n0;  // uniform
-  };
+  static constexpr bool GATHER = false;
+  typedef Sc Item;
 
   static __device__ __forceinline__ int wrow(int i) {
     const int a = i >> 3, hi = (i >> 2) & 1, b = i & 3;
@@ -306,10 +319,20 @@ struct DownOp {
   __device__ __forceinline__ const uint16_t* a_row(const Item& it, int r, int) const {
     return h + (size_t)(it.row0 + min(r, it.rows - 1)) * Is;
   }
-  __device__ __forceinline__ const uint16_t* b_row(const Item& it, int br) const {
+  __device__ __forceinline__ void setup_sc(const MTile& t, int nt, Sc& sc) const {
+    sc.g = uni(t.g);
+    sc.row0 = uni(t.row0);
+    sc.rows = uni(t.rows);
+    sc.n0 = uni(nt) * BN;
+  }
+  __device__ __forceinline__ const int32_t* idx_src(const Sc&, int) const { return nullptr; }
+  __device__ __forceinline__ const uint16_t* a_src(const Sc& sc, int r, const int32_t*) const {
+    return h + (size_t)(sc.row0 + min(r, sc.rows - 1)) * Is;
+  }
+  __device__ __forceinline__ const uint16_t* b_row(const Sc& it, int br) const {
     return w_dn + ((size_t)it.g * d + min(it.n0 + br, d - 1)) * Is;
   }
-  __device__ __forceinline__ void epilogue(const Item& it, f32x16 (&acc)[Tile<BN>::NB][2],
+  __device__ __forceinline__ void epilogue(const Sc& it, f32x16 (&acc)[Tile<BN>::NB][2],
                                            int mb_on) const {
     constexpr int NB = Tile<BN>::NB;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -344,6 +367,223 @@ __global__ __launch_bounds__(NT_) void down_bf16_kernel(DownOp<BN> op,
   run_items<BN>(op, tiles, hdr, op.Is, n_tiles_n);
 }
 
+// ---------------------------------------------------------------- DMA ring driver
+// Same tiles and MFMA schedule, but the operand slabs travel global -> LDS directly
+// (global_load_lds_dwordx4: lane i of a wave deposits its 16 bytes at LDS base + 16 i),
+// through a ring of NS stages of 32 K-elements each, D = NS - 1 stages ahead of the MFMAs.
+// Nothing passes through registers, so several stages can be in flight; the waits are
+// explicit (s_waitcnt vmcnt counts this wave's outstanding copies, oldest first) and one
+// s_barrier per stage both publishes the stage that landed and frees the one just used.
+// The ring runs across item boundaries.  For the gate-up GEMM the slot list entries of the
+// next tile (which tokens to gather) are copied into LDS the same way, one item ahead.
+constexpr int SK = 32;  // K elements per stage: 64 bytes per row, 4 chunks of 16 bytes
+
+// chunk c (0..3) of row r sits at position c ^ g(r); 16 lanes read 16 rows at one chunk
+// index, rows of equal r & 3 share banks, so g must differ over them (see swz above)
+template <int MODE>
+__device__ __forceinline__ int swz32(int r, int c) {
+  const int g = MODE == SWZ_SEQ ? ((r >> 2) & 3) : (((r >> 2) & 1) | (((r >> 4) & 1) << 1));
+  return r * SK + ((c ^ g) << 3);
+}
+template <int MODE>
+__device__ __forceinline__ int chunk_of(int r, int pos) {  // inverse: which chunk sits at pos
+  const int g = MODE == SWZ_SEQ ? ((r >> 2) & 3) : (((r >> 2) & 1) | (((r >> 4) & 1) << 1));
+  return pos ^ g;
+}
+
+template <int BN>
+struct Ring {
+  static constexpr int NS = BN == 192 ? 5 : 4;  // stages in LDS
+  static constexpr int D = NS - 1;              // stages in flight ahead of the MFMAs
+  static constexpr int NB = BN / 2 / 32;
+  static constexpr int A_ST = BM * SK, B_ST = BN * SK, STAGE = A_ST + B_ST;  // elements
+  static constexpr size_t PAIR_BYTES = 2 * BM * sizeof(int32_t);
+  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE * 2 + PAIR_BYTES;
+  // 16-row copy instructions per wave and stage for the weight rows
+  static __device__ __forceinline__ int nb_dma(int wv) { return BN == 256 ? 2 : (wv < 4 ? 2 : 1); }
+  static __device__ __forceinline__ int b_block(int wv, int j) {
+    return BN == 256 ? 2 * wv + j : (wv < 4 ? 2 * wv + j : 8 + (wv - 4));
+  }
+};
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// one wave-wide copy: every lane fetches 16 (4) bytes at g; lane i's data lands at lds + 16 i (4 i)
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds)
+               : "memory");
+}
+__device__ __forceinline__ void dma4(const void* g, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 1\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds)
+               : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_copies() {  // until at most N of this wave's copies are pending
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BN, class Op>
+__device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restrict__ tiles,
+                                              const int32_t* __restrict__ hdr, int K,
+                                              int n_tiles_n) {
+  using RG = Ring<BN>;
+  constexpr int NS = RG::NS, D = RG::D, NB = RG::NB;
+  extern __shared__ __align__(16) uint16_t smem[];
+  int32_t* pair_lds = reinterpret_cast<int32_t*>(smem + (size_t)NS * RG::STAGE);  // [2][BM]
+  const int lane = threadIdx.x & 63, wv = uni(threadIdx.x >> 6);
+  const int wm = wv >> 1, wn = wv & 1;
+  const int wrow = Op::wrow(lane & 31);
+  const int total_items = hdr[HDR_MTILES] * n_tiles_n;
+  const ItemRange ir = xcd_items(total_items);
+  if (ir.begin >= ir.end) return;  // uniform over the workgroup
+  const int n_my = (ir.end - ir.begin + ir.step - 1) / ir.step;
+  const int nst = K / SK;  // K % 32 == 0 for every supported shape
+  const int total = n_my * nst;
+  const uint32_t smem_base = lds_addr(smem);
+  const uint32_t pair_base = lds_addr(pair_lds);
+
+  // rows this lane copies: 16-row block `blk` of the tile, row blk*16 + lane/4, position lane%4
+  const int sub = lane >> 2, pos = lane & 3;
+  const int nbd = RG::nb_dma(wv);
+
+  Sc cur, nxt;
+  auto load_sc = [&](int my_idx, Sc& sc) {
+    const int item = ir.begin + my_idx * ir.step;
+    op.setup_sc(tiles[item / n_tiles_n], item % n_tiles_n, sc);
+  };
+  // copy the slot-list entries of an item's rows into pair_lds[parity] (waves 0..3, 64 rows each)
+  auto fetch_pairs = [&](const Sc& sc, int parity) {
+    if (Op::GATHER && wv < 4)
+      dma4(op.idx_src(sc, wv * 64 + lane), pair_base + (uint32_t)(parity * BM + wv * 64) * 4);
+  };
+  const uint16_t* pa[2];
+  const uint16_t* pb[2];
+  auto producer_rows = [&](const Sc& sc, int parity) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int r = wv * 32 + j * 16 + sub;
+      pa[j] = op.a_src(sc, r, pair_lds + parity * BM) + chunk_of<SWZ_SEQ>(r, pos) * 8;
+      const int br = RG::b_block(wv, j) * 16 + sub;
+      pb[j] = op.b_row(sc, br) + chunk_of<Op::WSWZ>(br, pos) * 8;
+    }
+  };
+  auto issue_stage = [&](int slot, int k0) {
+    const uint32_t sa = smem_base + (uint32_t)slot * (RG::STAGE * 2);
+    const uint32_t sb = sa + RG::A_ST * 2;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) dma16(pa[j] + k0, sa + (uint32_t)(wv * 32 + j * 16) * (SK * 2));
+    dma16(pb[0] + k0, sb + (uint32_t)(RG::b_block(wv, 0) * 16) * (SK * 2));
+    if (nbd == 2) dma16(pb[1] + k0, sb + (uint32_t)(RG::b_block(wv, 1) * 16) * (SK * 2));
+  };
+
+  // ---- prologue
+  load_sc(0, cur);
+  nxt = cur;
+  if (n_my > 1) load_sc(1, nxt);
+  fetch_pairs(cur, 0);
+  wait_copies<0>();
+  __builtin_amdgcn_s_barrier();
+  producer_rows(cur, 0);
+  if (n_my > 1) fetch_pairs(nxt, 1);
+  int p = 0, p_stage = 0, p_item = 0, p_slot = 0;  // producer: global stage, stage in item, item, ring slot
+  for (; p < D && p < total; ++p) {                // nst >= D: all inside the first item
+    issue_stage(p_slot, p_stage * SK);
+    ++p_stage;
+    p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
+  }
+
+  f32x16 acc[NB][2];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+  int mb_on = (cur.rows - wm * 64 + 31) / 32;
+  mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+
+  int c_stage = 0, c_item = 0, c_slot = 0;
+  for (int q = 0; q < total; ++q) {
+    // stage q has landed once at most the copies of the D - 1 younger stages are pending
+    if (p - q - 1 >= D - 1) {
+      if (nbd == 2) wait_copies<(D - 1) * 4>(); else wait_copies<(D - 1) * 3>();
+    } else {
+      wait_copies<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    if (p < total) {
+      if (p_stage == nst) {  // the producer enters the next item
+        p_stage = 0;
+        ++p_item;
+        producer_rows(nxt, p_item & 1);
+      }
+      issue_stage(p_slot, p_stage * SK);
+      ++p;
+      ++p_stage;
+      p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
+    }
+    // ---- MFMAs of stage q
+    {
+      const uint16_t* sa = smem + (size_t)c_slot * RG::STAGE;
+      const uint16_t* sb = sa + RG::A_ST;
+#pragma unroll
+      for (int ks = 0; ks < SK / 16; ++ks) {
+        const int c = ks * 2 + (lane >> 5);
+        bf16x8 ft[2], fw[NB];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+          ft[mb] = *reinterpret_cast<const bf16x8*>(sa + swz32<SWZ_SEQ>(wm * 64 + mb * 32 + (lane & 31), c));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          fw[nb] = *reinterpret_cast<const bf16x8*>(sb + swz32<Op::WSWZ>(wn * (BN / 2) + nb * 32 + wrow, c));
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+          if (mb < mb_on) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[nb], ft[mb], acc[nb][mb], 0, 0, 0);
+          }
+        }
+      }
+    }
+    c_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
+    if (++c_stage == nst) {  // the item is complete
+      op.epilogue(cur, acc, mb_on);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+      c_stage = 0;
+      ++c_item;
+      cur = nxt;
+      mb_on = (cur.rows - wm * 64 + 31) / 32;
+      mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+      if (c_item + 1 < n_my) {
+        load_sc(c_item + 1, nxt);
+        fetch_pairs(nxt, (c_item + 1) & 1);
+      }
+    }
+  }
+}
+
+template <int BN>
+__global__ __launch_bounds__(NT_) void gate_up_bf16_dma_kernel(GateUpOp<BN> op,
+                                                               const MTile* __restrict__ tiles,
+                                                               const int32_t* __restrict__ hdr,
+                                                               int n_tiles_n) {
+  run_items_dma<BN>(op, tiles, hdr, op.d, n_tiles_n);
+}
+template <int BN>
+__global__ __launch_bounds__(NT_) void down_bf16_dma_kernel(DownOp<BN> op,
+                                                            const MTile* __restrict__ tiles,
+                                                            const int32_t* __restrict__ hdr,
+                                                            int n_tiles_n) {
+  run_items_dma<BN>(op, tiles, hdr, op.Is, n_tiles_n);
+}
+
 // ---------------------------------------------------------------- launchers
 // The tiles need more than the default 64 KiB of dynamic LDS (the CU has 160 KiB).
 template <class Kern>
@@ -362,18 +602,29 @@ hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const in
                                const MTile* tiles, const int32_t* hdr, uint16_t* h, int T, int d,
                                int Is, int k_max, int max_mtiles, hipStream_t s) {
   hipError_t e;
+  // the ring needs the next tile's slot-list entries one item ahead: K/32 >= 2 D - 1 stages
   if (pick_bn(Is, 128, 96) == 128) {
     GateUpOp<256> op{x, w_gu, sorted_pair, h, T, d, Is, k_max};
     const int ntn = cdiv(Is, 128);
-    if ((e = allow_lds(gate_up_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
-    gate_up_bf16_kernel<256><<<persistent_grid((long)max_mtiles * ntn, 1), NT_,
-                               Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
+    if (d / SK >= 2 * Ring<256>::D - 1) {
+      if ((e = allow_lds(gate_up_bf16_dma_kernel<256>, Ring<256>::LDS_BYTES)) != hipSuccess) return e;
+      gate_up_bf16_dma_kernel<256><<<grid, NT_, Ring<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    } else {
+      if ((e = allow_lds(gate_up_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
+      gate_up_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    }
   } else {
     GateUpOp<192> op{x, w_gu, sorted_pair, h, T, d, Is, k_max};
     const int ntn = cdiv(Is, 96);
-    if ((e = allow_lds(gate_up_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
-    gate_up_bf16_kernel<192><<<persistent_grid((long)max_mtiles * ntn, 1), NT_,
-                               Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
+    if (d / SK >= 2 * Ring<192>::D - 1) {
+      if ((e = allow_lds(gate_up_bf16_dma_kernel<192>, Ring<192>::LDS_BYTES)) != hipSuccess) return e;
+      gate_up_bf16_dma_kernel<192><<<grid, NT_, Ring<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    } else {
+      if ((e = allow_lds(gate_up_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
+      gate_up_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    }
   }
   return hipGetLastError();
 }
@@ -382,18 +633,29 @@ hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile
                             const int32_t* hdr, uint16_t* y, int d, int Is, int max_mtiles,
                             hipStream_t s) {
   hipError_t e;
+  // the ring keeps D stages in flight inside one item or the next: K/32 >= D stages per item
   if (pick_bn(d, 256, 192) == 256) {
     DownOp<256> op{h, w_dn, y, d, Is};
     const int ntn = cdiv(d, 256);
-    if ((e = allow_lds(down_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
-    down_bf16_kernel<256><<<persistent_grid((long)max_mtiles * ntn, 1), NT_, Tile<256>::LDS_BYTES,
-                            s>>>(op, tiles, hdr, ntn);
+    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
+    if (Is / SK >= Ring<256>::NS) {
+      if ((e = allow_lds(down_bf16_dma_kernel<256>, Ring<256>::LDS_BYTES)) != hipSuccess) return e;
+      down_bf16_dma_kernel<256><<<grid, NT_, Ring<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    } else {
+      if ((e = allow_lds(down_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
+      down_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    }
   } else {
     DownOp<192> op{h, w_dn, y, d, Is};
     const int ntn = cdiv(d, 192);
-    if ((e = allow_lds(down_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
-    down_bf16_kernel<192><<<persistent_grid((long)max_mtiles * ntn, 1), NT_, Tile<192>::LDS_BYTES,
-                            s>>>(op, tiles, hdr, ntn);
+    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
+    if (Is / SK >= Ring<192>::NS) {
+      if ((e = allow_lds(down_bf16_dma_kernel<192>, Ring<192>::LDS_BYTES)) != hipSuccess) return e;
+      down_bf16_dma_kernel<192><<<grid, NT_, Ring<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    } else {
+      if ((e = allow_lds(down_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
+      down_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    }
   }
   return hipGetLastError();
 }

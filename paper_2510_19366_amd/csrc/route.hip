@@ -61,10 +61,11 @@ __global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
                                                      int32_t* __restrict__ hdr, int T, int d,
                                                      int E) {
   static_assert((BM / TM) * (BN / TN) == 256, "256 threads");
-  static_assert(TM % 4 == 0 && TN % 4 == 0, "float4 operands");
+  static_assert((TM % 4 == 0 || TM < 4) && (TN % 4 == 0 || TN < 4), "float4 or scalar operands");
   constexpr int LDA = BM + 4, LDB = BN + 4;
-  constexpr int A8 = BM * LG_BK / 8 / 256;  // 8-element loads per thread
+  constexpr int A8 = (BM * LG_BK / 8 + 255) / 256;  // 8-element loads per thread
   constexpr int B8 = (BN * LG_BK / 8 + 255) / 256;
+  constexpr int GM = TM < 4 ? TM : 4, GN = TN < 4 ? TN : 4;  // contiguous outputs per group
   __shared__ float As[LG_BK * LDA];
   __shared__ float Bs[LG_BK * LDB];
 
@@ -84,8 +85,10 @@ __global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
 #pragma unroll
     for (int i = 0; i < A8; ++i) {
       int c = tid + i * 256;  // chunk id: row = c / 4, k-chunk = c % 4
-      int row = min(m0 + c / (LG_BK / 8), T - 1);
-      load8<InT>(x + (size_t)row * d + k0 + (c % (LG_BK / 8)) * 8, pa[i]);
+      if (c < BM * LG_BK / 8) {
+        int row = min(m0 + c / (LG_BK / 8), T - 1);
+        load8<InT>(x + (size_t)row * d + k0 + (c % (LG_BK / 8)) * 8, pa[i]);
+      }
     }
 #pragma unroll
     for (int i = 0; i < B8; ++i) {
@@ -100,9 +103,11 @@ __global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
 #pragma unroll
     for (int i = 0; i < A8; ++i) {
       int c = tid + i * 256;
-      int r = c / (LG_BK / 8), kc = (c % (LG_BK / 8)) * 8;
+      if (c < BM * LG_BK / 8) {
+        int r = c / (LG_BK / 8), kc = (c % (LG_BK / 8)) * 8;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) As[(kc + e) * LDA + r] = pa[i][e];
+        for (int e = 0; e < 8; ++e) As[(kc + e) * LDA + r] = pa[i][e];
+      }
     }
 #pragma unroll
     for (int i = 0; i < B8; ++i) {
@@ -124,15 +129,25 @@ __global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
 #pragma unroll
     for (int kk = 0; kk < LG_BK; ++kk) {
       float a[TM], b[TN];
+      if constexpr (GM == 4) {
 #pragma unroll
-      for (int h = 0; h < TM / 4; ++h) {
-        float4 v = *reinterpret_cast<const float4*>(&As[kk * LDA + h * (BM * 4 / TM) + ty * 4]);
-        a[4 * h] = v.x; a[4 * h + 1] = v.y; a[4 * h + 2] = v.z; a[4 * h + 3] = v.w;
+        for (int h = 0; h < TM / 4; ++h) {
+          float4 v = *reinterpret_cast<const float4*>(&As[kk * LDA + h * (BM * 4 / TM) + ty * 4]);
+          a[4 * h] = v.x; a[4 * h + 1] = v.y; a[4 * h + 2] = v.z; a[4 * h + 3] = v.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = As[kk * LDA + ty * TM + i];
       }
+      if constexpr (GN == 4) {
 #pragma unroll
-      for (int h = 0; h < TN / 4; ++h) {
-        float4 v = *reinterpret_cast<const float4*>(&Bs[kk * LDB + h * (BN * 4 / TN) + tx * 4]);
-        b[4 * h] = v.x; b[4 * h + 1] = v.y; b[4 * h + 2] = v.z; b[4 * h + 3] = v.w;
+        for (int h = 0; h < TN / 4; ++h) {
+          float4 v = *reinterpret_cast<const float4*>(&Bs[kk * LDB + h * (BN * 4 / TN) + tx * 4]);
+          b[4 * h] = v.x; b[4 * h + 1] = v.y; b[4 * h + 2] = v.z; b[4 * h + 3] = v.w;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = Bs[kk * LDB + tx * TN + j];
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -143,23 +158,23 @@ __global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
 
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    int row = m0 + (i / 4) * (BM * 4 / TM) + ty * 4 + (i % 4);
+    int row = m0 + (GM == 4 ? (i / 4) * (BM * 4 / TM) + ty * 4 + (i % 4) : ty * TM + i);
     if (row >= T) continue;
 #pragma unroll
-    for (int h = 0; h < TN / 4; ++h) {
-      int col = n0 + h * (BN * 4 / TN) + tx * 4;
-      float v[4];
+    for (int h = 0; h < TN / GN; ++h) {
+      int col = n0 + (GN == 4 ? h * (BN * 4 / TN) + tx * 4 : tx * TN);
+      float v[GN];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        v[j] = acc[i][4 * h + j];
+      for (int j = 0; j < GN; ++j) {
+        v[j] = acc[i][GN * h + j];
         if (bias != nullptr && col + j < E) v[j] = v[j] + bias[col + j];
       }
-      if (col + 3 < E && (E % 4) == 0) {
+      if (GN == 4 && col + 3 < E && (E % 4) == 0) {
         *reinterpret_cast<float4*>(&logits[(size_t)row * E + col]) =
-            make_float4(v[0], v[1], v[2], v[3]);
+            make_float4(v[0], v[1], v[2], v[GN - 1]);
       } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < GN; ++j)
           if (col + j < E) logits[(size_t)row * E + col + j] = v[j];
       }
     }
@@ -174,23 +189,26 @@ hipError_t launch_logits(int dtype, const void* x, const void* w, const float* b
     clear_flags_kernel<<<1, 1, 0, s>>>(hdr);
     return hipGetLastError();
   }
-  if (E > 64) {
-    dim3 grid(cdiv(E, 128), cdiv(T, 128));
-    if (dtype == 0)
-      logits_kernel<float, 128, 128, 8, 8><<<grid, 256, 0, s>>>(
-          (const float*)x, (const float*)w, bias, logits, hdr, T, d, E);
-    else
-      logits_kernel<uint16_t, 128, 128, 8, 8><<<grid, 256, 0, s>>>(
-          (const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E);
-  } else {
-    dim3 grid(cdiv(E, 32), cdiv(T, 128));
-    if (dtype == 0)
-      logits_kernel<float, 128, 32, 4, 4><<<grid, 256, 0, s>>>(
-          (const float*)x, (const float*)w, bias, logits, hdr, T, d, E);
-    else
-      logits_kernel<uint16_t, 128, 32, 4, 4><<<grid, 256, 0, s>>>(
-          (const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E);
-  }
+  // Largest tile that still gives every CU work: the per-logit chains are long (d dependent
+  // FMAs), so with few sub-experts or tokens small tiles spread them over more waves.
+#define MP_LOGITS(BM_, BN_, TM_, TN_)                                                        \
+  do {                                                                                       \
+    dim3 grid(cdiv(E, BN_), cdiv(T, BM_));                                                   \
+    if (dtype == 0)                                                                          \
+      logits_kernel<float, BM_, BN_, TM_, TN_><<<grid, 256, 0, s>>>(                         \
+          (const float*)x, (const float*)w, bias, logits, hdr, T, d, E);                     \
+    else                                                                                     \
+      logits_kernel<uint16_t, BM_, BN_, TM_, TN_><<<grid, 256, 0, s>>>(                      \
+          (const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E);               \
+  } while (0)
+  const long cus = num_cus();
+  if ((long)cdiv(E, 128) * cdiv(T, 128) >= cus + cus / 2)
+    MP_LOGITS(128, 128, 8, 8);
+  else if ((long)cdiv(E, 64) * cdiv(T, 64) >= cus)
+    MP_LOGITS(64, 64, 4, 4);
+  else
+    MP_LOGITS(32, 32, 2, 2);
+#undef MP_LOGITS
   return hipGetLastError();
 }
 
