@@ -370,7 +370,7 @@ __global__ __launch_bounds__(NT_) void down_bf16_kernel(DownOp<BN> op,
 // ---------------------------------------------------------------- DMA ring driver
 // Same tiles and MFMA schedule, but the operand slabs travel global -> LDS directly
 // (global_load_lds_dwordx4: lane i of a wave deposits its 16 bytes at LDS base + 16 i),
-// through a ring of NS stages of 32 K-elements each, D = NS - 1 stages ahead of the MFMAs.
+// through a ring of NS stages of 32 K-elements each, NS - 1 stages ahead of the MFMAs.
 // Nothing passes through registers, so several stages can be in flight; the waits are
 // explicit (s_waitcnt vmcnt counts this wave's outstanding copies, oldest first) and one
 // s_barrier per stage both publishes the stage that landed and frees the one just used.
@@ -477,6 +477,22 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
     if (nbd == 2) dma16(pb[1] + k0, sb + (uint32_t)(RG::b_block(wv, 1) * 16) * (SK * 2));
   };
 
+  // fragments of one K step of 16 from ring slot `slot`
+  struct Frag {
+    bf16x8 t[2], w[NB];
+  };
+  auto read_frags = [&](int slot, int ks, Frag& f) {
+    const uint16_t* sa = smem + (size_t)slot * RG::STAGE;
+    const uint16_t* sb = sa + RG::A_ST;
+    const int c = ks * 2 + (lane >> 5);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+      f.t[mb] = *reinterpret_cast<const bf16x8*>(sa + swz32<SWZ_SEQ>(wm * 64 + mb * 32 + (lane & 31), c));
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+      f.w[nb] = *reinterpret_cast<const bf16x8*>(sb + swz32<Op::WSWZ>(wn * (BN / 2) + nb * 32 + wrow, c));
+  };
+
   // ---- prologue
   load_sc(0, cur);
   nxt = cur;
@@ -486,12 +502,17 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   __builtin_amdgcn_s_barrier();
   producer_rows(cur, 0);
   if (n_my > 1) fetch_pairs(nxt, 1);
-  int p = 0, p_stage = 0, p_item = 0, p_slot = 0;  // producer: global stage, stage in item, item, ring slot
-  for (; p < D && p < total; ++p) {                // nst >= D: all inside the first item
+  // producer: global stage, stage in item, item, ring slot.  It runs NS - 1 stages ahead of
+  // the MFMAs: stage q is being multiplied, stage q + 1 has landed (its first fragments are
+  // read early), stages q + 2 .. q + NS - 1 are in flight.
+  int p = 0, p_stage = 0, p_item = 0, p_slot = 0;
+  for (; p < NS - 1 && p < total; ++p) {  // nst >= NS: all inside the first item
     issue_stage(p_slot, p_stage * SK);
     ++p_stage;
     p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
   }
+  if (nbd == 2) wait_copies<(NS - 2) * 4>(); else wait_copies<(NS - 2) * 3>();  // stage 0 landed
+  __builtin_amdgcn_s_barrier();
 
   f32x16 acc[NB][2];
 #pragma unroll
@@ -503,15 +524,18 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   int mb_on = (cur.rows - wm * 64 + 31) / 32;
   mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
 
+  Frag f0, f1;
+  read_frags(0, 0, f0);
   int c_stage = 0, c_item = 0, c_slot = 0;
   for (int q = 0; q < total; ++q) {
-    // stage q has landed once at most the copies of the D - 1 younger stages are pending
-    if (p - q - 1 >= D - 1) {
-      if (nbd == 2) wait_copies<(D - 1) * 4>(); else wait_copies<(D - 1) * 3>();
+    const int n_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
+    // stage q + 1 has landed once at most the copies of the NS - 3 younger stages are pending
+    if (p - q - 2 >= NS - 3) {
+      if (nbd == 2) wait_copies<(NS - 3) * 4>(); else wait_copies<(NS - 3) * 3>();
     } else {
       wait_copies<0>();
     }
-    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
     if (p < total) {
       if (p_stage == nst) {  // the producer enters the next item
         p_stage = 0;
@@ -523,31 +547,26 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
       ++p_stage;
       p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
     }
-    // ---- MFMAs of stage q
-    {
-      const uint16_t* sa = smem + (size_t)c_slot * RG::STAGE;
-      const uint16_t* sb = sa + RG::A_ST;
+    // ---- MFMAs of stage q; the first fragments of stage q + 1 are fetched in between.
+    // A wave whose 64 slot rows are all beyond the tile's rows skips the MFMAs (the tile
+    // takes as long as its fullest wave, so finer skipping would buy nothing).
+    read_frags(c_slot, 1, f1);
+    if (mb_on > 0) {
 #pragma unroll
-      for (int ks = 0; ks < SK / 16; ++ks) {
-        const int c = ks * 2 + (lane >> 5);
-        bf16x8 ft[2], fw[NB];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-          ft[mb] = *reinterpret_cast<const bf16x8*>(sa + swz32<SWZ_SEQ>(wm * 64 + mb * 32 + (lane & 31), c));
+      for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          fw[nb] = *reinterpret_cast<const bf16x8*>(sb + swz32<Op::WSWZ>(wn * (BN / 2) + nb * 32 + wrow, c));
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-          if (mb < mb_on) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-              acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[nb], ft[mb], acc[nb][mb], 0, 0, 0);
-          }
-        }
-      }
+          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.w[nb], f0.t[mb], acc[nb][mb], 0, 0, 0);
     }
-    c_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
+    if (q + 1 < total) read_frags(n_slot, 0, f0);
+    if (mb_on > 0) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.w[nb], f1.t[mb], acc[nb][mb], 0, 0, 0);
+    }
+    c_slot = n_slot;
     if (++c_stage == nst) {  // the item is complete
       op.epilogue(cur, acc, mb_on);
 #pragma unroll
