@@ -32,7 +32,7 @@ template <> struct Vec<1> {
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+      w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
     *reinterpret_cast<uint4*>(static_cast<uint16_t*>(base) + elem) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
@@ -45,6 +45,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
                                                       void* __restrict__ out, int d, int k_max,
                                                       int n_rows) {
   constexpr int N = Vec<DT>::N;
+  constexpr int RU = 4;  // rows fetched before any is consumed
   const int t = blockIdx.x;
   int kt = k_tok[t];
   kt = kt < 0 ? 0 : (kt > k_max ? k_max : kt);
@@ -53,18 +54,18 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
   for (int col = threadIdx.x * N; col < d; col += 256 * N) {
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int j = 0;
-    for (; j + 4 <= kt; j += 4) {  // four rows in flight, still added in ascending j
-      float v[4][8];
-      float wj[4];
+    for (; j + RU <= kt; j += RU) {  // RU rows in flight, still added in ascending j
+      float v[RU][8];
+      float wj[RU];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < RU; ++u) {
         int sl = slots[j + u];
         bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing
         wj[u] = ok ? wt[j + u] : 0.0f;
         Vec<DT>::load(y, (size_t)(ok ? sl : 0) * d + col, v[u]);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < RU; ++u)
 #pragma unroll
         for (int e = 0; e < N; ++e) acc[e] = fmaf(wj[u], v[u][e], acc[e]);
     }

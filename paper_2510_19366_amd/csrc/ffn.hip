@@ -47,7 +47,9 @@ __global__ __launch_bounds__(TILES_THREADS) void ffn_tiles_kernel(const int32_t*
       t.g = g;
       t.row0 = lo + i * FFN_BM;
       t.rows = min(FFN_BM, n - i * FFN_BM);
-      t.pad = 0;
+      t.first = first;
+      t.count = min(nt, max_tiles - first);  // never points past the table
+      t.pad[0] = t.pad[1] = t.pad[2] = 0;
       if (first + i < max_tiles) tiles[first + i] = t;
     }
     __syncthreads();

@@ -123,9 +123,7 @@ struct Pipe {
 __device__ __forceinline__ float silu_mul(float a, float u) {
   return __fdividef(a, 1.0f + __expf(-a)) * u;
 }
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return pack_bf16x2(a, b); }
 
 // What every lane knows about a work item: group, first slot row, valid rows, first
 // output column (or neuron) of the n-tile.  Wave-uniform.
@@ -448,9 +446,21 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   const int nbd = RG::nb_dma(wv);
 
   Sc cur, nxt;
+  // Item -> (m-tile, n-tile).  A group's items are contiguous; inside a group they are walked
+  // in chunks of C n-tiles x all of the group's m-tiles, so that the ~32 items an XCD works on
+  // at a time form a block a x b of m-tiles x n-tiles with a + b small: each activation tile
+  // is then fetched once for b n-tiles and each weight tile once for a m-tiles.
   auto load_sc = [&](int my_idx, Sc& sc) {
     const int item = ir.begin + my_idx * ir.step;
-    op.setup_sc(tiles[item / n_tiles_n], item % n_tiles_n, sc);
+    const MTile t0 = tiles[item / n_tiles_n];
+    const int first = uni(t0.first), cnt = uni(t0.count);
+    const int L = item - first * n_tiles_n;
+    int C = 32 / (cnt < 6 ? cnt : 6);
+    C = C > n_tiles_n ? n_tiles_n : C;
+    const int per = cnt * C;
+    const int c = L / per, r = L % per;
+    const int Cc = min(C, n_tiles_n - c * C);
+    op.setup_sc(tiles[first + r / Cc], c * C + r % Cc, sc);
   };
   // copy the slot-list entries of an item's rows into pair_lds[parity] (waves 0..3, 64 rows each)
   auto fetch_pairs = [&](const Sc& sc, int parity) {

@@ -11,8 +11,11 @@ enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_WORDS = 64 };
 
 constexpr int FFN_BM = 256;  // rows of one m-tile of the grouped GEMMs
 
-struct MTile {       // one m-tile of a group: rows [row0, row0 + rows) of the slot list
-  int32_t g, row0, rows, pad;
+struct MTile {  // one m-tile of a group: rows [row0, row0 + rows) of the slot list
+  int32_t g, row0, rows;
+  int32_t first;  // table index of the group's first m-tile
+  int32_t count;  // m-tiles of the group
+  int32_t pad[3];
 };
 
 inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
@@ -55,11 +58,12 @@ int num_cus();  // compute units of the current device (cached)
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
   return __uint_as_float(((uint32_t)b) << 16);
 }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// two fp32 -> two bf16 (round to nearest even) in one word, a in the low half: v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 }  // namespace mp
