@@ -181,7 +181,7 @@ __device__ __forceinline__ void run_items(const Op& op, const MTile* __restrict_
       else if (has_next)
         pipe.gload(op, nxt, 0, K);
       pipe.compute(buf, acc, mb_on, wrow);
-      if (last) op.epilogue(cur, acc, mb_on);
+      if (last) op.epilogue(cur, acc, mb_on, nullptr);
       if (!last || has_next) pipe.sstore(buf ^ 1);
       __syncthreads();
       buf ^= 1;
@@ -244,6 +244,13 @@ struct GateUpOp {
   __device__ __forceinline__ const int32_t* idx_src(const Sc& sc, int r) const {
     return sorted_pair + sc.row0 + min(r, sc.rows - 1);
   }
+  // store instructions a wave's epilogue issues (one per row block and weight block), if
+  // that is known exactly: every block of the wave inside the n-range; else 0
+  static constexpr int STORES_PER_MB = Tile<BN>::NB;
+  __device__ __forceinline__ int stores_issued(const Sc& sc, int mb_on, int, int wn) const {
+    const bool all = sc.n0 + wn * (BN / 4) + (Tile<BN>::NB - 1) * 16 < Is;
+    return all ? mb_on * STORES_PER_MB : 0;
+  }
   __device__ __forceinline__ const uint16_t* a_src(const Sc&, int r, const int32_t* pair_lds) const {
     const int tok = pair_lds[r] / k_max;
     return x + (size_t)min(max(tok, 0), T - 1) * d;
@@ -254,7 +261,7 @@ struct GateUpOp {
     return w_gu + ((size_t)it.g * 2 * Is + ((rr >> 4) ? Is + neuron : neuron)) * d;
   }
   __device__ __forceinline__ void epilogue(const Sc& it, f32x16 (&acc)[Tile<BN>::NB][2],
-                                           int mb_on) const {
+                                           int mb_on, uint16_t*) const {
     constexpr int NB = Tile<BN>::NB;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int wm = wv >> 1, wn = wv & 1;
@@ -324,14 +331,24 @@ struct DownOp {
     sc.n0 = uni(nt) * BN;
   }
   __device__ __forceinline__ const int32_t* idx_src(const Sc&, int) const { return nullptr; }
+  static constexpr int STORES_PER_MB = 2 * Tile<BN>::NB;
+  // a lower bound that is one of 0, STORES_PER_MB, 2 * STORES_PER_MB
+  __device__ __forceinline__ int stores_issued(const Sc& sc, int mb_on, int wm, int wn) const {
+    const bool all = sc.n0 + wn * (BN / 2) + (Tile<BN>::NB - 1) * 32 < d;
+    if (!all) return 0;
+    // the coalescing epilogue stores 8 rows per instruction: only full 32-row blocks count
+    const int full_blocks = min(max((sc.rows - wm * 64) / 32, 0), 2);
+    return (BN == 256 ? full_blocks : mb_on) * STORES_PER_MB;
+  }
   __device__ __forceinline__ const uint16_t* a_src(const Sc& sc, int r, const int32_t*) const {
     return h + (size_t)(sc.row0 + min(r, sc.rows - 1)) * Is;
   }
   __device__ __forceinline__ const uint16_t* b_row(const Sc& it, int br) const {
     return w_dn + ((size_t)it.g * d + min(it.n0 + br, d - 1)) * Is;
   }
-  __device__ __forceinline__ void epilogue(const Sc& it, f32x16 (&acc)[Tile<BN>::NB][2],
-                                           int mb_on) const {
+  // Direct form: a lane stores its 16 consecutive columns of one row (two 16-byte stores).
+  __device__ __forceinline__ void epilogue_direct(const Sc& it, f32x16 (&acc)[Tile<BN>::NB][2],
+                                                  int mb_on) const {
     constexpr int NB = Tile<BN>::NB;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int wm = wv >> 1, wn = wv & 1;
@@ -351,6 +368,48 @@ struct DownOp {
                                                              pack2(v[4], v[5]), pack2(v[6], v[7]));
           *reinterpret_cast<uint4*>(yrow + col + 8) = make_uint4(
               pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
+        }
+      }
+    }
+  }
+  // Coalescing form (BN = 256, wave-private 4 KiB of LDS): 32 rows x 64 columns at a time are
+  // written to LDS in the accumulator layout and read back row-major, so that every store
+  // instruction writes 8 rows x 128 contiguous bytes (whole cache lines) instead of 64
+  // scattered 16-byte pieces.  y is the layer's largest HBM stream.  LDS rows are 128 bytes,
+  // 16-byte chunk c of row r sits at position c ^ ((r >> 1) & 7): conflict-free both ways.
+  __device__ __forceinline__ void epilogue(const Sc& it, f32x16 (&acc)[Tile<BN>::NB][2], int mb_on,
+                                           uint16_t* scratch) const {
+    constexpr int NB = Tile<BN>::NB;
+    if (BN != 256 || scratch == nullptr) {
+      epilogue_direct(it, acc, mb_on);
+      return;
+    }
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int wm = wv >> 1, wn = wv & 1;
+    const int r = lane & 31, hi = lane >> 5;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      if (mb >= mb_on) continue;
+      const int valid = it.rows - (wm * 64 + mb * 32);  // rows of this block inside the tile
+#pragma unroll
+      for (int half = 0; half < NB / 2; ++half) {
+        const int col0 = it.n0 + wn * (BN / 2) + half * 64;
+        if (col0 >= d) continue;  // d % 64 == 0: a half is inside or outside as a whole
+#pragma unroll
+        for (int nbl = 0; nbl < 2; ++nbl) {
+          const f32x16 v = acc[half * 2 + nbl][mb];
+          const int c = nbl * 4 + 2 * hi, sw = (r >> 1) & 7;
+          *reinterpret_cast<uint4*>(scratch + r * 64 + (((c) ^ sw) << 3)) =
+              make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
+          *reinterpret_cast<uint4*>(scratch + r * 64 + (((c + 1) ^ sw) << 3)) = make_uint4(
+              pack2(v[8], v[9]), pack2(v[10], v[11]), pack2(v[12], v[13]), pack2(v[14], v[15]));
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int row = j * 8 + (lane >> 3), c = lane & 7;
+          const uint4 q = *reinterpret_cast<const uint4*>(scratch + row * 64 + ((c ^ ((row >> 1) & 7)) << 3));
+          if (row < valid)
+            *reinterpret_cast<uint4*>(y + (size_t)(it.row0 + wm * 64 + mb * 32 + row) * d + col0 + c * 8) = q;
         }
       }
     }
@@ -389,14 +448,20 @@ __device__ __forceinline__ int chunk_of(int r, int pos) {  // inverse: which chu
   return pos ^ g;
 }
 
-template <int BN>
+// LDS plan: NS ring stages, then the slot-list entries of two tiles (gate-up only), then
+// 4 KiB per wave of scratch for the coalescing epilogue (down only).
+constexpr int EPI_WAVE_BYTES = 4096;
+template <int BN, bool GATHER>
 struct Ring {
-  static constexpr int NS = BN == 192 ? 5 : 4;  // stages in LDS
+  static constexpr int NS = (BN == 192 && GATHER) ? 5 : 4;  // stages in LDS
   static constexpr int D = NS - 1;              // stages in flight ahead of the MFMAs
   static constexpr int NB = BN / 2 / 32;
   static constexpr int A_ST = BM * SK, B_ST = BN * SK, STAGE = A_ST + B_ST;  // elements
-  static constexpr size_t PAIR_BYTES = 2 * BM * sizeof(int32_t);
-  static constexpr size_t LDS_BYTES = (size_t)NS * STAGE * 2 + PAIR_BYTES;
+  static constexpr size_t RING_BYTES = (size_t)NS * STAGE * 2;
+  static constexpr size_t PAIR_BYTES = GATHER ? 2 * BM * sizeof(int32_t) : 0;
+  static constexpr size_t EPI_BYTES = GATHER ? 0 : (NT_ / 64) * EPI_WAVE_BYTES;
+  static constexpr size_t LDS_BYTES = RING_BYTES + PAIR_BYTES + EPI_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS per CU");
   // 16-row copy instructions per wave and stage for the weight rows
   static __device__ __forceinline__ int nb_dma(int wv) { return BN == 256 ? 2 : (wv < 4 ? 2 : 1); }
   static __device__ __forceinline__ int b_block(int wv, int j) {
@@ -421,15 +486,27 @@ __device__ __forceinline__ void wait_copies() {  // until at most N of this wave
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// wait until at most BASE + extra operations are pending; extra is 0, PER_MB or 2 * PER_MB
+template <int BASE, int PER_MB>
+__device__ __forceinline__ void wait_steady(int extra) {
+  if (extra == 2 * PER_MB)
+    wait_copies<BASE + 2 * PER_MB>();
+  else if (extra == PER_MB)
+    wait_copies<BASE + PER_MB>();
+  else
+    wait_copies<BASE>();
+}
+
 template <int BN, class Op>
 __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restrict__ tiles,
                                               const int32_t* __restrict__ hdr, int K,
                                               int n_tiles_n) {
-  using RG = Ring<BN>;
+  using RG = Ring<BN, Op::GATHER>;
   constexpr int NS = RG::NS, D = RG::D, NB = RG::NB;
   extern __shared__ __align__(16) uint16_t smem[];
   int32_t* pair_lds = reinterpret_cast<int32_t*>(smem + (size_t)NS * RG::STAGE);  // [2][BM]
   const int lane = threadIdx.x & 63, wv = uni(threadIdx.x >> 6);
+  uint16_t* epi_lds = RG::EPI_BYTES ? smem + (RG::RING_BYTES + RG::PAIR_BYTES) / 2 + (size_t)wv * (EPI_WAVE_BYTES / 2) : nullptr;
   const int wm = wv >> 1, wn = wv & 1;
   const int wrow = Op::wrow(lane & 31);
   const int total_items = hdr[HDR_MTILES] * n_tiles_n;
@@ -537,14 +614,21 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   Frag f0, f1;
   read_frags(0, 0, f0);
   int c_stage = 0, c_item = 0, c_slot = 0;
+  int st_credit = 0, st_count = 0;  // iterations left in which st_count stores may be pending
   for (int q = 0; q < total; ++q) {
     const int n_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
-    // stage q + 1 has landed once at most the copies of the NS - 3 younger stages are pending
+    // Stage q + 1 has landed once at most the operations issued after it are pending: the
+    // copies of the NS - 3 younger stages and, for NS - 2 iterations after an epilogue, that
+    // epilogue's stores (vector memory operations retire in issue order, loads and stores
+    // alike; counting the stores keeps the ring from draining behind every output tile).
     if (p - q - 2 >= NS - 3) {
-      if (nbd == 2) wait_copies<(NS - 3) * 4>(); else wait_copies<(NS - 3) * 3>();
+      const int extra = st_credit > 0 ? st_count : 0;
+      if (nbd == 2) wait_steady<(NS - 3) * 4, Op::STORES_PER_MB>(extra);
+      else wait_steady<(NS - 3) * 3, Op::STORES_PER_MB>(extra);
     } else {
       wait_copies<0>();
     }
+    st_credit = st_credit > 0 ? st_credit - 1 : 0;
     __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
     if (p < total) {
       if (p_stage == nst) {  // the producer enters the next item
@@ -578,7 +662,9 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
     }
     c_slot = n_slot;
     if (++c_stage == nst) {  // the item is complete
-      op.epilogue(cur, acc, mb_on);
+      op.epilogue(cur, acc, mb_on, epi_lds);
+      st_count = uni(op.stores_issued(cur, mb_on, wm, wn));
+      st_credit = NS - 2;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -636,9 +722,9 @@ hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const in
     GateUpOp<256> op{x, w_gu, sorted_pair, h, T, d, Is, k_max};
     const int ntn = cdiv(Is, 128);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (d / SK >= 2 * Ring<256>::D - 1) {
-      if ((e = allow_lds(gate_up_bf16_dma_kernel<256>, Ring<256>::LDS_BYTES)) != hipSuccess) return e;
-      gate_up_bf16_dma_kernel<256><<<grid, NT_, Ring<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    if (d / SK >= 2 * Ring<256, true>::D - 1) {
+      if ((e = allow_lds(gate_up_bf16_dma_kernel<256>, Ring<256, true>::LDS_BYTES)) != hipSuccess) return e;
+      gate_up_bf16_dma_kernel<256><<<grid, NT_, Ring<256, true>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
       if ((e = allow_lds(gate_up_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
       gate_up_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
@@ -647,9 +733,9 @@ hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const in
     GateUpOp<192> op{x, w_gu, sorted_pair, h, T, d, Is, k_max};
     const int ntn = cdiv(Is, 96);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (d / SK >= 2 * Ring<192>::D - 1) {
-      if ((e = allow_lds(gate_up_bf16_dma_kernel<192>, Ring<192>::LDS_BYTES)) != hipSuccess) return e;
-      gate_up_bf16_dma_kernel<192><<<grid, NT_, Ring<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    if (d / SK >= 2 * Ring<192, true>::D - 1) {
+      if ((e = allow_lds(gate_up_bf16_dma_kernel<192>, Ring<192, true>::LDS_BYTES)) != hipSuccess) return e;
+      gate_up_bf16_dma_kernel<192><<<grid, NT_, Ring<192, true>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
       if ((e = allow_lds(gate_up_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
       gate_up_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
@@ -667,9 +753,9 @@ hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile
     DownOp<256> op{h, w_dn, y, d, Is};
     const int ntn = cdiv(d, 256);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (Is / SK >= Ring<256>::NS) {
-      if ((e = allow_lds(down_bf16_dma_kernel<256>, Ring<256>::LDS_BYTES)) != hipSuccess) return e;
-      down_bf16_dma_kernel<256><<<grid, NT_, Ring<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    if (Is / SK >= Ring<256, false>::NS) {
+      if ((e = allow_lds(down_bf16_dma_kernel<256>, Ring<256, false>::LDS_BYTES)) != hipSuccess) return e;
+      down_bf16_dma_kernel<256><<<grid, NT_, Ring<256, false>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
       if ((e = allow_lds(down_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
       down_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
@@ -678,9 +764,9 @@ hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile
     DownOp<192> op{h, w_dn, y, d, Is};
     const int ntn = cdiv(d, 192);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (Is / SK >= Ring<192>::NS) {
-      if ((e = allow_lds(down_bf16_dma_kernel<192>, Ring<192>::LDS_BYTES)) != hipSuccess) return e;
-      down_bf16_dma_kernel<192><<<grid, NT_, Ring<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
+    if (Is / SK >= Ring<192, false>::NS) {
+      if ((e = allow_lds(down_bf16_dma_kernel<192>, Ring<192, false>::LDS_BYTES)) != hipSuccess) return e;
+      down_bf16_dma_kernel<192><<<grid, NT_, Ring<192, false>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
       if ((e = allow_lds(down_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
       down_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
