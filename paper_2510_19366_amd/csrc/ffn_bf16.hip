@@ -587,6 +587,7 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   fetch_pairs(cur, 0);
   wait_copies<0>();
   __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");  // LDS reads below must stay below the barrier
   producer_rows(cur, 0);
   if (n_my > 1) fetch_pairs(nxt, 1);
   // producer: global stage, stage in item, item, ring slot.  It runs NS - 1 stages ahead of
@@ -600,6 +601,7 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   }
   if (nbd == 2) wait_copies<(NS - 2) * 4>(); else wait_copies<(NS - 2) * 3>();  // stage 0 landed
   __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   f32x16 acc[NB][2];
 #pragma unroll
@@ -630,6 +632,7 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
     }
     st_credit = st_credit > 0 ? st_credit - 1 : 0;
     __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
+    asm volatile("" ::: "memory");
     if (p < total) {
       if (p_stage == nst) {  // the producer enters the next item
         p_stage = 0;
