@@ -46,6 +46,12 @@ def test_config1_tiny_f32_stage_by_stage():
     dict(T=333, d=128, N=3, S=2, Is=32, k_max=6),
     dict(T=1, d=64, N=2, S=2, Is=64, k_max=4),
     dict(T=1500, d=192, N=40, S=4, Is=160, k_max=20),
+    # long enough K for the global->LDS ring in both GEMMs; 96-neuron and 128-neuron tiles,
+    # a 192-column down tile (d = 320 pads less with 192), partial last n-tiles
+    dict(T=900, d=320, N=4, S=2, Is=224, k_max=5),
+    dict(T=2100, d=512, N=3, S=4, Is=352, k_max=7),
+    dict(T=600, d=256, N=2, S=1, Is=1024, k_max=2),
+    dict(T=500, d=128, N=4, S=2, Is=128, k_max=4),
 ])
 def test_small_cases_full_oracle(dtype, case):
     rng = np.random.default_rng(case["T"])
