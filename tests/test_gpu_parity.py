@@ -110,6 +110,32 @@ def test_wide_router_and_large_k():
     check_against_oracle(wl, r, ref)
 
 
+@pytest.mark.parametrize("scale", [1.0, 1e-19])
+def test_matrix_core_logits_are_the_same_chain(scale):
+    # large T x E takes the matrix-core logits kernel (one fused multiply-add per k and
+    # instruction); it must reproduce the oracle's binary32 chain bit for bit, ragged edges
+    # and subnormal partial sums (scale 1e-19: products ~1e-40) included
+    T, E, d = 6200, 1000, 192
+    rng = np.random.default_rng(11)
+    wl = W.make_workload("wide", dtype="f32", d=d, n_experts=E, n_sub=1, inter_sub=32,
+                         req_tokens=[T], req_k=[5], k_max=5, seed=11, w_std=0.05,
+                         with_weights=False)
+    wl.x = (wl.x * np.float32(scale)).astype(np.float32)
+    wl.w_router = (wl.w_router * np.float32(scale)).astype(np.float32)
+    bias = (rng.standard_normal(E) * scale * scale).astype(np.float32)
+    shape = B.make_shape(T, d, E, 1, 32, 5, "f32")
+    ws = B.alloc_workspace(shape)
+    x, wr = torch.from_numpy(wl.x).cuda(), torch.from_numpy(wl.w_router).cuda()
+    ids, w, lg = B.moe_prism_route(shape, x, wr, torch.from_numpy(bias).cuda(),
+                                   torch.from_numpy(wl.k_tok).cuda(), ws, want_logits=True)
+    torch.cuda.synchronize()
+    ref = O.logits(wl.x, wl.w_router, bias)
+    assert np.array_equal(to_np(lg).view(np.uint32), ref.view(np.uint32))
+    assert np.array_equal(to_np(ids), O.select(ref, wl.k_tok, 5))
+    if scale != 1.0:
+        assert np.any((np.abs(ref) < 1.2e-38) & (ref != 0))     # subnormal logits do occur
+
+
 def test_expand_k_and_errors():
     req_k = torch.tensor([3, 0, 5], dtype=torch.int32, device="cuda")
     req_off = torch.tensor([0, 4, 4, 9], dtype=torch.int32, device="cuda")
