@@ -50,7 +50,7 @@ static Layout layout_of(const moe_prism_shape* s) {
   const size_t T = (size_t)s->T, E = (size_t)s->n_experts * s->n_sub, km = (size_t)s->k_max;
   const size_t el = s->dtype == MOE_PRISM_F32 ? 4 : 2;
   const size_t rows = T * km;
-  L.n_chunks = cdiv((long)T, 64L * dispatch_chunk_words((int)E));
+  L.n_chunks = cdiv((long)T, 64L * dispatch_chunk_words((int)E, s->T));
   L.max_mtiles = (int)(rows / FFN_BM + E);
   size_t o = 0;
   auto take = [&](size_t bytes) {

@@ -14,9 +14,12 @@
 
 namespace mp {
 
-int dispatch_chunk_words(int E) {
-  int w = 8192 / (E > 0 ? E : 1);  // E * W * 8 bytes of LDS <= 64 KiB
-  if (w > 4) w = 4;
+int dispatch_chunk_words(int E, int T) {
+  int cap = 8192 / (E > 0 ? E : 1);  // E * W * 8 bytes of LDS <= 64 KiB
+  if (cap > 4) cap = 4;
+  if (cap < 1) cap = 1;
+  int w = T / (64 * 256);  // aim at >= 256 chunks (one per CU) before growing the chunks
+  if (w > cap) w = cap;
   if (w < 1) w = 1;
   return w;
 }
@@ -70,7 +73,19 @@ __global__ __launch_bounds__(SCAN_THREADS) void dispatch_scan_kernel(int32_t* __
     int g = g0 + tid;
     int run = 0;
     if (g < E) {
-      for (int c = 0; c < n_chunks; ++c) {
+      constexpr int U = 8;  // loads in flight per thread: the chain over chunks is latency bound
+      int c = 0;
+      for (; c + U <= n_chunks; c += U) {
+        int v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = chunk_cnt[(size_t)(c + u) * E + g];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          chunk_cnt[(size_t)(c + u) * E + g] = run;
+          run += v[u];
+        }
+      }
+      for (; c < n_chunks; ++c) {
         int v = chunk_cnt[(size_t)c * E + g];
         chunk_cnt[(size_t)c * E + g] = run;
         run += v;
@@ -129,7 +144,7 @@ __global__ __launch_bounds__(256) void dispatch_place_kernel(
 hipError_t launch_dispatch_count(const int32_t* ids, int32_t* chunk_cnt, int T, int E, int k_max,
                                  hipStream_t s) {
   if (T == 0) return hipSuccess;
-  int W = dispatch_chunk_words(E);
+  int W = dispatch_chunk_words(E, T);
   int nch = cdiv(T, 64 * W);
   dispatch_count_kernel<<<nch, 256, (size_t)E * W * 8, s>>>(ids, chunk_cnt, T, E, W, k_max);
   return hipGetLastError();
@@ -137,7 +152,7 @@ hipError_t launch_dispatch_count(const int32_t* ids, int32_t* chunk_cnt, int T, 
 
 hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int32_t* off, int32_t* hdr, int T,
                                 int E, hipStream_t s) {
-  int W = dispatch_chunk_words(E);
+  int W = dispatch_chunk_words(E, T);
   int nch = cdiv(T, 64 * W);
   dispatch_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(chunk_cnt, cnt, off, hdr, nch, E);
   return hipGetLastError();
@@ -147,7 +162,7 @@ hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, 
                                  int32_t* sorted_pair, int32_t* slot_of_pair, int T, int E,
                                  int k_max, hipStream_t s) {
   if (T == 0) return hipSuccess;
-  int W = dispatch_chunk_words(E);
+  int W = dispatch_chunk_words(E, T);
   int nch = cdiv(T, 64 * W);
   dispatch_place_kernel<<<nch, 256, (size_t)E * W * 8, s>>>(ids, chunk_base, off, sorted_pair,
                                                              slot_of_pair, T, E, W, k_max);

@@ -30,7 +30,7 @@ hipError_t launch_topk(const float* logits, const int32_t* k_tok, int32_t* ids, 
                        hipStream_t s);
 
 // dispatch: chunk_cnt is [n_chunks, E] scratch
-int dispatch_chunk_words(int E);                 // 64-token words per chunk
+int dispatch_chunk_words(int E, int T);          // 64-token words per chunk
 hipError_t launch_dispatch_count(const int32_t* ids, int32_t* chunk_cnt, int T, int E, int k_max,
                                  hipStream_t s);
 hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int32_t* off, int32_t* hdr, int T,

@@ -339,22 +339,34 @@ hipError_t launch_logits(int dtype, const void* x, const void* w, const float* b
 // wave-wide arg-max over the logits not yet taken, by (logit desc, id asc),
 // reduced with cross-lane shuffles; no sort and no global traffic besides the
 // logits row and the outputs.
-struct Best {
-  float v;
-  int g;
-};
-__device__ __forceinline__ Best better(Best a, Best b) {
-  return (b.v > a.v || (b.v == a.v && b.g < a.g)) ? b : a;
+// Wave-wide reductions that leave the result in every lane: four DPP steps inside each row
+// of 16 lanes (lane ^ 1, lane ^ 2, mirror inside 8, mirror inside 16), then the four row
+// results are read with v_readlane and combined.  No LDS traffic, unlike shuffles.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+  return __builtin_amdgcn_mov_dpp(v, CTRL, 0xf, 0xf, true);
 }
-__device__ __forceinline__ Best wave_best(Best x) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) {
-    Best o;
-    o.v = __shfl_xor(x.v, m, 64);
-    o.g = __shfl_xor(x.g, m, 64);
-    x = better(x, o);
-  }
-  return x;
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+__device__ __forceinline__ float wave_max_f(float v) {
+  v = fmaxf(v, __int_as_float(dpp_i<DPP_XOR1>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_i<DPP_XOR2>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_i<DPP_HALF_MIRROR>(__float_as_int(v))));
+  v = fmaxf(v, __int_as_float(dpp_i<DPP_MIRROR>(__float_as_int(v))));
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+__device__ __forceinline__ int wave_min_i(int v) {
+  v = min(v, dpp_i<DPP_XOR1>(v));
+  v = min(v, dpp_i<DPP_XOR2>(v));
+  v = min(v, dpp_i<DPP_HALF_MIRROR>(v));
+  v = min(v, dpp_i<DPP_MIRROR>(v));
+  const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+  const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+  return min(min(r0, r1), min(r2, r3));
 }
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
@@ -383,6 +395,7 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
   }
 
   const float NEG_INF = -__builtin_inff();
+  unsigned long long taken = 0ull;  // bit i: this lane's element i was picked
   float v[ELEMS];
   const float* row = logits + (size_t)t * E;
 #pragma unroll
@@ -391,11 +404,10 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
     v[i] = g < E ? row[g] : NEG_INF;
   }
   // full-softmax denominator (only needed when weights are not renormalised)
-  float mx = NEG_INF;
+  float lmax = NEG_INF;
 #pragma unroll
-  for (int i = 0; i < ELEMS; ++i) mx = fmaxf(mx, v[i]);
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  for (int i = 0; i < ELEMS; ++i) lmax = fmaxf(lmax, v[i]);
+  const float mx = wave_max_f(lmax);
   float denom = 0.0f;
   if (!renorm) {
 #pragma unroll
@@ -404,24 +416,42 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
     denom = wave_sum(denom);
   }
 
-  unsigned long long taken = 0ull;  // bit i: this lane's element i was picked
+  // Pick j: the wave-wide maximum of the lanes' best free logits, and among the lanes that
+  // hold it the smallest sub-expert id (equal logits, +0.0 == -0.0 included, go to the
+  // lower id).  g = 64 i + lane, so the winner's lane is g & 63.  Only that lane rescans.
+  const int NONE = 0x7fffffff;
+  float bv = NEG_INF;  // this lane's best free logit and its id
+  int bg = NONE;
+#pragma unroll
+  for (int i = 0; i < ELEMS; ++i) {
+    const int g = i * 64 + lane;
+    if (g < E && (bg == NONE || v[i] > bv)) {  // ascending g: strict > keeps the lower id
+      bv = v[i];
+      bg = g;
+    }
+  }
   float dsel = 0.0f;
   for (int j = 0; j < kt; ++j) {
-    Best b{NEG_INF, 0x7fffffff};
-#pragma unroll
-    for (int i = 0; i < ELEMS; ++i) {
-      int g = i * 64 + lane;
-      bool free_ = g < E && !((taken >> i) & 1ull);
-      Best c{v[i], g};
-      if (free_) b = better(b, c);  // ascending g inside a lane: strict > keeps the lower id
-    }
-    b = wave_best(b);
-    if ((b.g & 63) == lane) taken |= 1ull << (b.g >> 6);
-    float e = expf(b.v - mx);
+    const float top = wave_max_f(bg == NONE ? NEG_INF : bv);
+    const int g = wave_min_i((bg != NONE && bv == top) ? bg : NONE);
+    const float e = expf(top - mx);
     dsel += e;
     if (lane == 0) {
       se[j] = e;
-      sid[j] = b.g;
+      sid[j] = g;
+    }
+    if ((g & 63) == lane) {  // the winner retires its element and rescans its own logits
+      taken |= 1ull << (g >> 6);
+      bv = NEG_INF;
+      bg = NONE;
+#pragma unroll
+      for (int i = 0; i < ELEMS; ++i) {
+        const int gi = i * 64 + lane;
+        if (gi < E && !((taken >> i) & 1ull) && (bg == NONE || v[i] > bv)) {
+          bv = v[i];
+          bg = gi;
+        }
+      }
     }
   }
   if (renorm) denom = dsel;
