@@ -37,6 +37,10 @@ template <> struct Vec<1> {
   }
 };
 
+// The token's slots and weights are fetched once into LDS (one element per thread), so the
+// row loop below never waits for an index before it can issue its row loads.
+constexpr int CB_CHUNK = 1024;  // = the largest k_max the library accepts
+
 template <int DT>
 __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y,
                                                       const int32_t* __restrict__ slot_of_pair,
@@ -45,36 +49,37 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
                                                       void* __restrict__ out, int d, int k_max,
                                                       int n_rows) {
   constexpr int N = Vec<DT>::N;
-  constexpr int RU = 4;  // rows fetched before any is consumed
+  constexpr int RU = 8;  // rows fetched before any is consumed
+  __shared__ int32_t s_slot[CB_CHUNK];
+  __shared__ float s_w[CB_CHUNK];
   const int t = blockIdx.x;
   int kt = k_tok[t];
   kt = kt < 0 ? 0 : (kt > k_max ? k_max : kt);
-  const int32_t* slots = slot_of_pair + (size_t)t * k_max;
-  const float* wt = w + (size_t)t * k_max;
+  for (int j = threadIdx.x; j < kt; j += 256) {
+    const int sl = slot_of_pair[(size_t)t * k_max + j];
+    const bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing
+    s_slot[j] = ok ? sl : 0;
+    s_w[j] = ok ? w[(size_t)t * k_max + j] : 0.0f;
+  }
+  __syncthreads();
   for (int col = threadIdx.x * N; col < d; col += 256 * N) {
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int j = 0;
     for (; j + RU <= kt; j += RU) {  // RU rows in flight, still added in ascending j
       float v[RU][8];
-      float wj[RU];
+#pragma unroll
+      for (int u = 0; u < RU; ++u) Vec<DT>::load(y, (size_t)s_slot[j + u] * d + col, v[u]);
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
-        int sl = slots[j + u];
-        bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing
-        wj[u] = ok ? wt[j + u] : 0.0f;
-        Vec<DT>::load(y, (size_t)(ok ? sl : 0) * d + col, v[u]);
+        const float wj = s_w[j + u];
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] = fmaf(wj, v[u][e], acc[e]);
       }
-#pragma unroll
-      for (int u = 0; u < RU; ++u)
-#pragma unroll
-        for (int e = 0; e < N; ++e) acc[e] = fmaf(wj[u], v[u][e], acc[e]);
     }
     for (; j < kt; ++j) {
       float v[8];
-      int sl = slots[j];
-      bool ok = sl >= 0 && sl < n_rows;
-      float wj = ok ? wt[j] : 0.0f;
-      Vec<DT>::load(y, (size_t)(ok ? sl : 0) * d + col, v);
+      const float wj = s_w[j];
+      Vec<DT>::load(y, (size_t)s_slot[j] * d + col, v);
 #pragma unroll
       for (int e = 0; e < N; ++e) acc[e] = fmaf(wj, v[e], acc[e]);
     }
