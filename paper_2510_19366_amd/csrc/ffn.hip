@@ -56,7 +56,11 @@ __global__ __launch_bounds__(TILES_THREADS) void ffn_tiles_kernel(const int32_t*
     if (tid == TILES_THREADS - 1) carry = first + nt;
     __syncthreads();
   }
-  if (tid == 0) hdr[HDR_MTILES] = min(carry, max_tiles);
+  if (tid == 0) {
+    hdr[HDR_MTILES] = min(carry, max_tiles);
+    hdr[HDR_DYN_GATE_UP] = 0;
+    hdr[HDR_DYN_DOWN] = 0;
+  }
 }
 
 hipError_t launch_ffn_tiles(const int32_t* off, MTile* tiles, int32_t* hdr, int E, int max_tiles,
@@ -203,7 +207,7 @@ __global__ __launch_bounds__(256) void ffn_down_f32_kernel(const float* __restri
 
 // ---------------------------------------------------------------- launchers
 hipError_t launch_ffn_gate_up(int dtype, const void* x, const void* w_gu, const int32_t* sorted_pair,
-                              const MTile* tiles, const int32_t* hdr, void* h, int T, int d, int Is,
+                              const MTile* tiles, int32_t* hdr, void* h, int T, int d, int Is,
                               int k_max, int max_mtiles, hipStream_t s) {
   if (max_mtiles <= 0) return hipSuccess;
   if (dtype != 0)
@@ -216,7 +220,7 @@ hipError_t launch_ffn_gate_up(int dtype, const void* x, const void* w_gu, const 
 }
 
 hipError_t launch_ffn_down(int dtype, const void* h, const void* w_dn, const MTile* tiles,
-                           const int32_t* hdr, void* y, int d, int Is, int max_mtiles,
+                           int32_t* hdr, void* y, int d, int Is, int max_mtiles,
                            hipStream_t s) {
   if (max_mtiles <= 0) return hipSuccess;
   if (dtype != 0)

@@ -434,6 +434,7 @@ __global__ __launch_bounds__(NT_) void down_bf16_kernel(DownOp<BN> op,
 // The ring runs across item boundaries.  For the gate-up GEMM the slot list entries of the
 // next tile (which tokens to gather) are copied into LDS the same way, one item ahead.
 constexpr int SK = 32;  // K elements per stage: 64 bytes per row, 4 chunks of 16 bytes
+constexpr int DYN_DIV = 8;  // 1/DYN_DIV of the work items go to the shared pool
 
 // chunk c (0..3) of row r sits at position c ^ g(r); 16 lanes read 16 rows at one chunk
 // index, rows of equal r & 3 share banks, so g must differ over them (see swz above)
@@ -499,8 +500,8 @@ __device__ __forceinline__ void wait_steady(int extra) {
 
 template <int BN, class Op>
 __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restrict__ tiles,
-                                              const int32_t* __restrict__ hdr, int K,
-                                              int n_tiles_n) {
+                                              int32_t* __restrict__ hdr, int K, int n_tiles_n,
+                                              int dyn_word) {
   using RG = Ring<BN, Op::GATHER>;
   constexpr int NS = RG::NS, D = RG::D, NB = RG::NB;
   extern __shared__ __align__(16) uint16_t smem[];
@@ -509,12 +510,19 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   uint16_t* epi_lds = RG::EPI_BYTES ? smem + (RG::RING_BYTES + RG::PAIR_BYTES) / 2 + (size_t)wv * (EPI_WAVE_BYTES / 2) : nullptr;
   const int wm = wv >> 1, wn = wv & 1;
   const int wrow = Op::wrow(lane & 31);
+  // Work split: the first 1 - 1/DYN_DIV of the item list is dealt out statically (XCD-aware,
+  // see xcd_items), the rest is a pool that workgroups draw from in batches once their own
+  // share is done, which evens out the finishing times (m-tiles differ in their row counts).
+  // The draw is an atomic with a returned value, so it sits between two pipeline runs, where
+  // no copy is in flight that the wait for the returned value could serialise.  The drawn index
+  // reaches the other waves through the first word of the (then idle) ring.
+  int32_t* dyn_next = reinterpret_cast<int32_t*>(smem);
   const int total_items = hdr[HDR_MTILES] * n_tiles_n;
-  const ItemRange ir = xcd_items(total_items);
-  if (ir.begin >= ir.end) return;  // uniform over the workgroup
-  const int n_my = (ir.end - ir.begin + ir.step - 1) / ir.step;
+  const int n_static = total_items - total_items / DYN_DIV;
   const int nst = K / SK;  // K % 32 == 0 for every supported shape
-  const int total = n_my * nst;
+  const int batch = nst >= 24 ? 1 : (24 + nst - 1) / nst;
+  ItemRange ir = xcd_items(n_static);
+  int n_my = ir.begin < ir.end ? (ir.end - ir.begin + ir.step - 1) / ir.step : 0;
   const uint32_t smem_base = lds_addr(smem);
   const uint32_t pair_base = lds_addr(pair_lds);
 
@@ -580,126 +588,140 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
       f.w[nb] = *reinterpret_cast<const bf16x8*>(sb + swz32<Op::WSWZ>(wn * (BN / 2) + nb * 32 + wrow, c));
   };
 
-  // ---- prologue
-  load_sc(0, cur);
-  nxt = cur;
-  if (n_my > 1) load_sc(1, nxt);
-  fetch_pairs(cur, 0);
-  wait_copies<0>();
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");  // LDS reads below must stay below the barrier
-  producer_rows(cur, 0);
-  if (n_my > 1) fetch_pairs(nxt, 1);
-  // producer: global stage, stage in item, item, ring slot.  It runs NS - 1 stages ahead of
-  // the MFMAs: stage q is being multiplied, stage q + 1 has landed (its first fragments are
-  // read early), stages q + 2 .. q + NS - 1 are in flight.
-  int p = 0, p_stage = 0, p_item = 0, p_slot = 0;
-  for (; p < NS - 1 && p < total; ++p) {  // nst >= NS: all inside the first item
-    issue_stage(p_slot, p_stage * SK);
-    ++p_stage;
-    p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
-  }
-  if (nbd == 2) wait_copies<(NS - 2) * 4>(); else wait_copies<(NS - 2) * 3>();  // stage 0 landed
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-
-  f32x16 acc[NB][2];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
-  int mb_on = (cur.rows - wm * 64 + 31) / 32;
-  mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
-
-  Frag f0, f1;
-  read_frags(0, 0, f0);
-  int c_stage = 0, c_item = 0, c_slot = 0;
-  int st_credit = 0, st_count = 0;  // iterations left in which st_count stores may be pending
-  for (int q = 0; q < total; ++q) {
-    const int n_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
-    // Stage q + 1 has landed once at most the operations issued after it are pending: the
-    // copies of the NS - 3 younger stages and, for NS - 2 iterations after an epilogue, that
-    // epilogue's stores (vector memory operations retire in issue order, loads and stores
-    // alike; counting the stores keeps the ring from draining behind every output tile).
-    if (p - q - 2 >= NS - 3) {
-      const int extra = st_credit > 0 ? st_count : 0;
-      if (nbd == 2) wait_steady<(NS - 3) * 4, Op::STORES_PER_MB>(extra);
-      else wait_steady<(NS - 3) * 3, Op::STORES_PER_MB>(extra);
-    } else {
-      wait_copies<0>();
-    }
-    st_credit = st_credit > 0 ? st_credit - 1 : 0;
-    __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
-    asm volatile("" ::: "memory");
-    if (p < total) {
-      if (p_stage == nst) {  // the producer enters the next item
-        p_stage = 0;
-        ++p_item;
-        producer_rows(nxt, p_item & 1);
-      }
+  for (;;) {
+  if (n_my > 0) {
+    const int total = n_my * nst;
+    // ---- prologue of one pipeline run over n_my items
+    load_sc(0, cur);
+    nxt = cur;
+    if (n_my > 1) load_sc(1, nxt);
+    fetch_pairs(cur, 0);
+    wait_copies<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");  // LDS reads below must stay below the barrier
+    producer_rows(cur, 0);
+    if (n_my > 1) fetch_pairs(nxt, 1);
+    // producer: global stage, stage in item, item, ring slot.  It runs NS - 1 stages ahead of
+    // the MFMAs: stage q is being multiplied, stage q + 1 has landed (its first fragments are
+    // read early), stages q + 2 .. q + NS - 1 are in flight.
+    int p = 0, p_stage = 0, p_item = 0, p_slot = 0;
+    for (; p < NS - 1 && p < total; ++p) {  // nst >= NS: all inside the first item
       issue_stage(p_slot, p_stage * SK);
-      ++p;
       ++p_stage;
       p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
     }
-    // ---- MFMAs of stage q; the first fragments of stage q + 1 are fetched in between.
-    // A wave whose 64 slot rows are all beyond the tile's rows skips the MFMAs (the tile
-    // takes as long as its fullest wave, so finer skipping would buy nothing).
-    read_frags(c_slot, 1, f1);
-    if (mb_on > 0) {
-#pragma unroll
+    if (nbd == 2) wait_copies<(NS - 2) * 4>(); else wait_copies<(NS - 2) * 3>();  // stage 0 landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    f32x16 acc[NB][2];
+  #pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+  #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.w[nb], f0.t[mb], acc[nb][mb], 0, 0, 0);
-    }
-    if (q + 1 < total) read_frags(n_slot, 0, f0);
-    if (mb_on > 0) {
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.w[nb], f1.t[mb], acc[nb][mb], 0, 0, 0);
-    }
-    c_slot = n_slot;
-    if (++c_stage == nst) {  // the item is complete
-      op.epilogue(cur, acc, mb_on, epi_lds);
-      st_count = uni(op.stores_issued(cur, mb_on, wm, wn));
-      st_credit = NS - 2;
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
+  #pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+    int mb_on = (cur.rows - wm * 64 + 31) / 32;
+    mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+
+    Frag f0, f1;
+    read_frags(0, 0, f0);
+    int c_stage = 0, c_item = 0, c_slot = 0;
+    int st_credit = 0, st_count = 0;  // iterations left in which st_count stores may be pending
+    for (int q = 0; q < total; ++q) {
+      const int n_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
+      // Stage q + 1 has landed once at most the operations issued after it are pending: the
+      // copies of the NS - 3 younger stages and, for NS - 2 iterations after an epilogue, that
+      // epilogue's stores (vector memory operations retire in issue order, loads and stores
+      // alike; counting the stores keeps the ring from draining behind every output tile).
+      if (p - q - 2 >= NS - 3) {
+        const int extra = st_credit > 0 ? st_count : 0;
+        if (nbd == 2) wait_steady<(NS - 3) * 4, Op::STORES_PER_MB>(extra);
+        else wait_steady<(NS - 3) * 3, Op::STORES_PER_MB>(extra);
+      } else {
+        wait_copies<0>();
+      }
+      st_credit = st_credit > 0 ? st_credit - 1 : 0;
+      __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
+      asm volatile("" ::: "memory");
+      if (p < total) {
+        if (p_stage == nst) {  // the producer enters the next item
+          p_stage = 0;
+          ++p_item;
+          producer_rows(nxt, p_item & 1);
+        }
+        issue_stage(p_slot, p_stage * SK);
+        ++p;
+        ++p_stage;
+        p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
+      }
+      // ---- MFMAs of stage q; the first fragments of stage q + 1 are fetched in between.
+      // A wave whose 64 slot rows are all beyond the tile's rows skips the MFMAs (the tile
+      // takes as long as its fullest wave, so finer skipping would buy nothing).
+      read_frags(c_slot, 1, f1);
+      if (mb_on > 0) {
+  #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
-      c_stage = 0;
-      ++c_item;
-      cur = nxt;
-      mb_on = (cur.rows - wm * 64 + 31) / 32;
-      mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
-      if (c_item + 1 < n_my) {
-        load_sc(c_item + 1, nxt);
-        fetch_pairs(nxt, (c_item + 1) & 1);
+  #pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.w[nb], f0.t[mb], acc[nb][mb], 0, 0, 0);
+      }
+      if (q + 1 < total) read_frags(n_slot, 0, f0);
+      if (mb_on > 0) {
+  #pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+  #pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.w[nb], f1.t[mb], acc[nb][mb], 0, 0, 0);
+      }
+      c_slot = n_slot;
+      if (++c_stage == nst) {  // the item is complete
+        op.epilogue(cur, acc, mb_on, epi_lds);
+        st_count = uni(op.stores_issued(cur, mb_on, wm, wn));
+        st_credit = NS - 2;
+  #pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+  #pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+  #pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+        c_stage = 0;
+        ++c_item;
+        cur = nxt;
+        mb_on = (cur.rows - wm * 64 + 31) / 32;
+        mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+        if (c_item + 1 < n_my) {
+          load_sc(c_item + 1, nxt);
+          fetch_pairs(nxt, (c_item + 1) & 1);
+        }
       }
     }
+  }
+    // ---- next batch from the pool (every copy of this run has landed, every wave is here)
+    __syncthreads();
+    if (threadIdx.x == 0) *dyn_next = atomicAdd(&hdr[dyn_word], batch);
+    __syncthreads();
+    ir.begin = n_static + uni(*dyn_next);  // read before this wave reaches the next run's first barrier
+    if (ir.begin >= total_items) break;
+    ir.end = min(total_items, ir.begin + batch);
+    ir.step = 1;
+    n_my = ir.end - ir.begin;
   }
 }
 
 template <int BN>
 __global__ __launch_bounds__(NT_) void gate_up_bf16_dma_kernel(GateUpOp<BN> op,
                                                                const MTile* __restrict__ tiles,
-                                                               const int32_t* __restrict__ hdr,
+                                                               int32_t* __restrict__ hdr,
                                                                int n_tiles_n) {
-  run_items_dma<BN>(op, tiles, hdr, op.d, n_tiles_n);
+  run_items_dma<BN>(op, tiles, hdr, op.d, n_tiles_n, HDR_DYN_GATE_UP);
 }
 template <int BN>
 __global__ __launch_bounds__(NT_) void down_bf16_dma_kernel(DownOp<BN> op,
                                                             const MTile* __restrict__ tiles,
-                                                            const int32_t* __restrict__ hdr,
+                                                            int32_t* __restrict__ hdr,
                                                             int n_tiles_n) {
-  run_items_dma<BN>(op, tiles, hdr, op.Is, n_tiles_n);
+  run_items_dma<BN>(op, tiles, hdr, op.Is, n_tiles_n, HDR_DYN_DOWN);
 }
 
 // ---------------------------------------------------------------- launchers
@@ -717,7 +739,7 @@ static int pick_bn(int n, int wide, int narrow) {
 }
 
 hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const int32_t* sorted_pair,
-                               const MTile* tiles, const int32_t* hdr, uint16_t* h, int T, int d,
+                               const MTile* tiles, int32_t* hdr, uint16_t* h, int T, int d,
                                int Is, int k_max, int max_mtiles, hipStream_t s) {
   hipError_t e;
   // the ring needs the next tile's slot-list entries one item ahead: K/32 >= 2 D - 1 stages
@@ -748,7 +770,7 @@ hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const in
 }
 
 hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile* tiles,
-                            const int32_t* hdr, uint16_t* y, int d, int Is, int max_mtiles,
+                            int32_t* hdr, uint16_t* y, int d, int Is, int max_mtiles,
                             hipStream_t s) {
   hipError_t e;
   // the ring keeps D stages in flight inside one item or the next: K/32 >= D stages per item

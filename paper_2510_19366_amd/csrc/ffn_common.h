@@ -33,10 +33,10 @@ inline int persistent_grid(long max_items, int per_cu) {  // a multiple of N_XCD
 
 // bf16 kernels (ffn_bf16.hip)
 hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const int32_t* sorted_pair,
-                               const MTile* tiles, const int32_t* hdr, uint16_t* h, int T, int d,
+                               const MTile* tiles, int32_t* hdr, uint16_t* h, int T, int d,
                                int Is, int k_max, int max_mtiles, hipStream_t s);
 hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile* tiles,
-                            const int32_t* hdr, uint16_t* y, int d, int Is, int max_mtiles,
+                            int32_t* hdr, uint16_t* y, int d, int Is, int max_mtiles,
                             hipStream_t s);
 
 }  // namespace mp

@@ -7,7 +7,8 @@
 namespace mp {
 
 // Workspace header: int32 words at the start of ws.
-enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_WORDS = 64 };
+// HDR_DYN_*: cursors of the FFN kernels' work pools (cleared with the m-tile table)
+enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_DYN_GATE_UP = 3, HDR_DYN_DOWN = 4, HDR_WORDS = 64 };
 
 constexpr int FFN_BM = 256;  // rows of one m-tile of the grouped GEMMs
 
@@ -43,10 +44,10 @@ hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, 
 hipError_t launch_ffn_tiles(const int32_t* off, MTile* tiles, int32_t* hdr, int E, int max_tiles,
                             int n_rows, hipStream_t s);
 hipError_t launch_ffn_gate_up(int dtype, const void* x, const void* w_gu, const int32_t* sorted_pair,
-                              const MTile* tiles, const int32_t* hdr, void* h, int T, int d, int Is,
+                              const MTile* tiles, int32_t* hdr, void* h, int T, int d, int Is,
                               int k_max, int max_mtiles, hipStream_t s);
 hipError_t launch_ffn_down(int dtype, const void* h, const void* w_dn, const MTile* tiles,
-                           const int32_t* hdr, void* y, int d, int Is, int max_mtiles,
+                           int32_t* hdr, void* y, int d, int Is, int max_mtiles,
                            hipStream_t s);
 
 hipError_t launch_combine(int dtype, const void* y, const int32_t* slot_of_pair, const float* w,
