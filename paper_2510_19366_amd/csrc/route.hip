@@ -226,25 +226,32 @@ __global__ __launch_bounds__(256) void logits_mfma_kernel(const InT* __restrict_
 
   // loader: 16-byte chunk lc of rows lr + 64 i
   const int lc = tid & 3, lr = tid >> 2;
-  const unsigned char* src[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = lr + 64 * i;
+  auto row_src = [&](int row) {
     const InT* base = row < 128 ? x + (size_t)min(m0 + row, T - 1) * d
                                 : w + (size_t)min(n0 + row - 128, E - 1) * d;
-    src[i] = reinterpret_cast<const unsigned char*>(base) + lc * 16;
-  }
-  uint4 pre[4];
-  auto gload = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      pre[i] = *reinterpret_cast<const uint4*>(src[i] + (size_t)k0 * sizeof(InT));
+    return reinterpret_cast<const unsigned char*>(base) + lc * 16;
   };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint4*>(&sm[buf][(lr + 64 * i) * LM_ROWB + lc * 16]) = pre[i];
-  };
+  const unsigned char* src0 = row_src(lr);
+  const unsigned char* src1 = row_src(lr + 64);
+  const unsigned char* src2 = row_src(lr + 128);
+  const unsigned char* src3 = row_src(lr + 192);
+  uint4 pre0, pre1, pre2, pre3;  // named registers: an indexed array here ends up in scratch memory
+#define LM_GLOAD(k0_)                                                                   \
+  do {                                                                                  \
+    const size_t o_ = (size_t)(k0_) * sizeof(InT);                                      \
+    pre0 = *reinterpret_cast<const uint4*>(src0 + o_);                                  \
+    pre1 = *reinterpret_cast<const uint4*>(src1 + o_);                                  \
+    pre2 = *reinterpret_cast<const uint4*>(src2 + o_);                                  \
+    pre3 = *reinterpret_cast<const uint4*>(src3 + o_);                                  \
+  } while (0)
+#define LM_SSTORE(buf_)                                                                 \
+  do {                                                                                  \
+    unsigned char* b_ = &sm[buf_][lr * LM_ROWB + lc * 16];                              \
+    *reinterpret_cast<uint4*>(b_) = pre0;                                               \
+    *reinterpret_cast<uint4*>(b_ + 64 * LM_ROWB) = pre1;                                \
+    *reinterpret_cast<uint4*>(b_ + 128 * LM_ROWB) = pre2;                               \
+    *reinterpret_cast<uint4*>(b_ + 192 * LM_ROWB) = pre3;                               \
+  } while (0)
 
   f32x32 acc0, acc1;
 #pragma unroll
@@ -254,13 +261,13 @@ __global__ __launch_bounds__(256) void logits_mfma_kernel(const InT* __restrict_
   }
   const int a_off = (wm * 64 + lane) * LM_ROWB, b_off = (128 + wn * 64 + lane) * LM_ROWB;
 
-  gload(0);
-  sstore(0);
+  LM_GLOAD(0);
+  LM_SSTORE(0);
   __syncthreads();
   int buf = 0;
   for (int k0 = 0; k0 < d; k0 += KB) {  // d % 64 == 0, so d % KB == 0
     const bool more = k0 + KB < d;
-    if (more) gload(k0 + KB);
+    if (more) LM_GLOAD(k0 + KB);
     uint4 qa[4], qb[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -273,7 +280,7 @@ __global__ __launch_bounds__(256) void logits_mfma_kernel(const InT* __restrict_
       acc0 = __builtin_amdgcn_mfma_f32_32x32x1f32(a, b, acc0, 1, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_32x32x1f32(a, b, acc1, 1, 1, 0);
     }
-    if (more) sstore(buf ^ 1);
+    if (more) LM_SSTORE(buf ^ 1);
     __syncthreads();
     buf ^= 1;
   }
@@ -294,6 +301,8 @@ __global__ __launch_bounds__(256) void logits_mfma_kernel(const InT* __restrict_
       }
     }
   }
+#undef LM_GLOAD
+#undef LM_SSTORE
 }
 
 __global__ void clear_flags_kernel(int32_t* hdr) { hdr[HDR_FLAGS] = 0; }
