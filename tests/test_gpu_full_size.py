@@ -67,7 +67,7 @@ def test_c2_mixtral_8x4_full():
     check_full(wl, n_sample=24)
 
 
-@pytest.mark.parametrize("T", [2048, 16384])
+@pytest.mark.parametrize("T", [512, 2048, 16384, 65536])
 def test_c5_matched_budget_split_vs_whole(T):
     # Sec. 3.2.2: repeated-row gate at k = S*k_orig with scale S reproduces the undivided layer
     a = W.config("c5a_s1_k8", T=T)
