@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--tokens", type=int, default=None, help="token count for the c5 sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--graph", action="store_true",
+                    help="additionally time the same steps replayed from one captured HIP graph "
+                         "(reported as graph_ms_per_step; the headline numbers stay the eager ones)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (known traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -130,6 +133,20 @@ def main():
         "stage_gbs": {k: v / (kern_ms[k] * 1e-3) / 1e9 for k, v in stage_bytes.items()
                       if kern_ms.get(k, 0) > 0},
     }
+
+    if args.graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        res["graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / args.steps
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O

@@ -725,11 +725,20 @@ __global__ __launch_bounds__(NT_) void down_bf16_dma_kernel(DownOp<BN> op,
 }
 
 // ---------------------------------------------------------------- launchers
-// The tiles need more than the default 64 KiB of dynamic LDS (the CU has 160 KiB).
-template <class Kern>
-static hipError_t allow_lds(Kern kern, size_t bytes) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+// The tiles need more than the default 64 KiB of dynamic LDS (the CU has 160 KiB).  The
+// attribute is set once per kernel and device, so the launch path makes no other runtime call
+// (which also keeps it usable while the caller's stream is being captured into a graph,
+// after one eager call).
+template <auto Kern>
+static hipError_t allow_lds(size_t bytes) {
+  static bool done[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+  if (dev >= 0 && done[dev]) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && dev >= 0) done[dev] = true;
+  return e;
 }
 
 // tile width (in units) with the least padding of n; ties go to the wider tile
@@ -748,10 +757,10 @@ hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const in
     const int ntn = cdiv(Is, 128);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
     if (d / SK >= 2 * Ring<256, true>::D - 1) {
-      if ((e = allow_lds(gate_up_bf16_dma_kernel<256>, Ring<256, true>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<gate_up_bf16_dma_kernel<256>>(Ring<256, true>::LDS_BYTES)) != hipSuccess) return e;
       gate_up_bf16_dma_kernel<256><<<grid, NT_, Ring<256, true>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
-      if ((e = allow_lds(gate_up_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<gate_up_bf16_kernel<256>>(Tile<256>::LDS_BYTES)) != hipSuccess) return e;
       gate_up_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     }
   } else {
@@ -759,10 +768,10 @@ hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const in
     const int ntn = cdiv(Is, 96);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
     if (d / SK >= 2 * Ring<192, true>::D - 1) {
-      if ((e = allow_lds(gate_up_bf16_dma_kernel<192>, Ring<192, true>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<gate_up_bf16_dma_kernel<192>>(Ring<192, true>::LDS_BYTES)) != hipSuccess) return e;
       gate_up_bf16_dma_kernel<192><<<grid, NT_, Ring<192, true>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
-      if ((e = allow_lds(gate_up_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<gate_up_bf16_kernel<192>>(Tile<192>::LDS_BYTES)) != hipSuccess) return e;
       gate_up_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     }
   }
@@ -779,10 +788,10 @@ hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile
     const int ntn = cdiv(d, 256);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
     if (Is / SK >= Ring<256, false>::NS) {
-      if ((e = allow_lds(down_bf16_dma_kernel<256>, Ring<256, false>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<down_bf16_dma_kernel<256>>(Ring<256, false>::LDS_BYTES)) != hipSuccess) return e;
       down_bf16_dma_kernel<256><<<grid, NT_, Ring<256, false>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
-      if ((e = allow_lds(down_bf16_kernel<256>, Tile<256>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<down_bf16_kernel<256>>(Tile<256>::LDS_BYTES)) != hipSuccess) return e;
       down_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     }
   } else {
@@ -790,10 +799,10 @@ hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile
     const int ntn = cdiv(d, 192);
     const int grid = persistent_grid((long)max_mtiles * ntn, 1);
     if (Is / SK >= Ring<192, false>::NS) {
-      if ((e = allow_lds(down_bf16_dma_kernel<192>, Ring<192, false>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<down_bf16_dma_kernel<192>>(Ring<192, false>::LDS_BYTES)) != hipSuccess) return e;
       down_bf16_dma_kernel<192><<<grid, NT_, Ring<192, false>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     } else {
-      if ((e = allow_lds(down_bf16_kernel<192>, Tile<192>::LDS_BYTES)) != hipSuccess) return e;
+      if ((e = allow_lds<down_bf16_kernel<192>>(Tile<192>::LDS_BYTES)) != hipSuccess) return e;
       down_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
     }
   }
