@@ -21,172 +21,16 @@ hipError_t launch_expand_k(int R, int T, const int32_t* req_k, const int32_t* re
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- logits
-// Each thread owns a TM x TN block of logits and walks the hidden index in
-// ascending order with one fused multiply-add per step, so every logit is the
-// same binary32 chain regardless of tiling.  x and w_router tiles are widened to
-// fp32 (exact for bf16) and staged through LDS, k-major, so that a thread reads
-// its operands as float4.
-template <typename T> struct Elem;
-template <> struct Elem<float> { static constexpr int per16 = 4; };
-template <> struct Elem<uint16_t> { static constexpr int per16 = 8; };
-
-template <typename InT>
-__device__ __forceinline__ void load8(const InT* p, float (&v)[8]);
-template <>
-__device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
-  float4 a = *reinterpret_cast<const float4*>(p);
-  float4 b = *reinterpret_cast<const float4*>(p + 4);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-  v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-template <>
-__device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float (&v)[8]) {
-  uint4 a = *reinterpret_cast<const uint4*>(p);
-  uint32_t w[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    v[2 * i] = __uint_as_float(w[i] << 16);
-    v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-  }
-}
-
-constexpr int LG_BK = 32;
-
-template <typename InT, int BM, int BN, int TM, int TN>
-__global__ __launch_bounds__(256) void logits_kernel(const InT* __restrict__ x,
-                                                     const InT* __restrict__ w,
-                                                     const float* __restrict__ bias,
-                                                     float* __restrict__ logits,
-                                                     int32_t* __restrict__ hdr, int T, int d,
-                                                     int E) {
-  static_assert((BM / TM) * (BN / TN) == 256, "256 threads");
-  static_assert((TM % 4 == 0 || TM < 4) && (TN % 4 == 0 || TN < 4), "float4 or scalar operands");
-  constexpr int LDA = BM + 4, LDB = BN + 4;
-  constexpr int A8 = (BM * LG_BK / 8 + 255) / 256;  // 8-element loads per thread
-  constexpr int B8 = (BN * LG_BK / 8 + 255) / 256;
-  constexpr int GM = TM < 4 ? TM : 4, GN = TN < 4 ? TN : 4;  // contiguous outputs per group
-  __shared__ float As[LG_BK * LDA];
-  __shared__ float Bs[LG_BK * LDB];
-
-  const int tid = threadIdx.x;
-  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) hdr[HDR_FLAGS] = 0;
-  const int tx = tid % (BN / TN), ty = tid / (BN / TN);
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-
-  float acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
-
-  float pa[A8][8], pb[B8][8];
-  auto gload = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < A8; ++i) {
-      int c = tid + i * 256;  // chunk id: row = c / 4, k-chunk = c % 4
-      if (c < BM * LG_BK / 8) {
-        int row = min(m0 + c / (LG_BK / 8), T - 1);
-        load8<InT>(x + (size_t)row * d + k0 + (c % (LG_BK / 8)) * 8, pa[i]);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < B8; ++i) {
-      int c = tid + i * 256;
-      if (c < BN * LG_BK / 8) {
-        int row = min(n0 + c / (LG_BK / 8), E - 1);
-        load8<InT>(w + (size_t)row * d + k0 + (c % (LG_BK / 8)) * 8, pb[i]);
-      }
-    }
-  };
-  auto sstore = [&]() {
-#pragma unroll
-    for (int i = 0; i < A8; ++i) {
-      int c = tid + i * 256;
-      if (c < BM * LG_BK / 8) {
-        int r = c / (LG_BK / 8), kc = (c % (LG_BK / 8)) * 8;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) As[(kc + e) * LDA + r] = pa[i][e];
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < B8; ++i) {
-      int c = tid + i * 256;
-      if (c < BN * LG_BK / 8) {
-        int r = c / (LG_BK / 8), kc = (c % (LG_BK / 8)) * 8;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) Bs[(kc + e) * LDB + r] = pb[i][e];
-      }
-    }
-  };
-
-  gload(0);
-  for (int k0 = 0; k0 < d; k0 += LG_BK) {
-    __syncthreads();
-    sstore();
-    __syncthreads();
-    if (k0 + LG_BK < d) gload(k0 + LG_BK);
-#pragma unroll
-    for (int kk = 0; kk < LG_BK; ++kk) {
-      float a[TM], b[TN];
-      if constexpr (GM == 4) {
-#pragma unroll
-        for (int h = 0; h < TM / 4; ++h) {
-          float4 v = *reinterpret_cast<const float4*>(&As[kk * LDA + h * (BM * 4 / TM) + ty * 4]);
-          a[4 * h] = v.x; a[4 * h + 1] = v.y; a[4 * h + 2] = v.z; a[4 * h + 3] = v.w;
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = As[kk * LDA + ty * TM + i];
-      }
-      if constexpr (GN == 4) {
-#pragma unroll
-        for (int h = 0; h < TN / 4; ++h) {
-          float4 v = *reinterpret_cast<const float4*>(&Bs[kk * LDB + h * (BN * 4 / TN) + tx * 4]);
-          b[4 * h] = v.x; b[4 * h + 1] = v.y; b[4 * h + 2] = v.z; b[4 * h + 3] = v.w;
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = Bs[kk * LDB + tx * TN + j];
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
-    }
-  }
-
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    int row = m0 + (GM == 4 ? (i / 4) * (BM * 4 / TM) + ty * 4 + (i % 4) : ty * TM + i);
-    if (row >= T) continue;
-#pragma unroll
-    for (int h = 0; h < TN / GN; ++h) {
-      int col = n0 + (GN == 4 ? h * (BN * 4 / TN) + tx * 4 : tx * TN);
-      float v[GN];
-#pragma unroll
-      for (int j = 0; j < GN; ++j) {
-        v[j] = acc[i][GN * h + j];
-        if (bias != nullptr && col + j < E) v[j] = v[j] + bias[col + j];
-      }
-      if (GN == 4 && col + 3 < E && (E % 4) == 0) {
-        *reinterpret_cast<float4*>(&logits[(size_t)row * E + col]) =
-            make_float4(v[0], v[1], v[2], v[GN - 1]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < GN; ++j)
-          if (col + j < E) logits[(size_t)row * E + col + j] = v[j];
-      }
-    }
-  }
-}
-
 // ---------------------------------------------------------------- logits on the matrix cores
-// v_mfma_f32_32x32x1_2b_f32 adds ONE k term per instruction: D = a * b + D, a fused
-// multiply-add with one rounding per output (checked on the device against fmaf chains of
-// 4096 terms, subnormal sums included: bit-identical).  Issuing it once per k in ascending
-// order therefore computes exactly the same binary32 chain as the vector kernel above, at
-// twice the rate of unpacked v_fma_f32.  No split-K, no reordering.
+// Every logit is ONE chain of d binary32 fused multiply-adds over the hidden index in
+// ascending order, then the fp32 bias add: the fixed summation order is what makes the
+// routing reproducible bit for bit.  The rank-1 fp32 MFMA forms add ONE k term per
+// instruction, D = a * b + D with one rounding per output (checked on the device against
+// fmaf chains of 4096 terms, subnormal sums included: bit-identical), so issuing one per k in
+// ascending order computes exactly that chain, at twice the rate of unpacked v_fma_f32.  No
+// split-K, no reordering.
+//
+// Large problems: v_mfma_f32_32x32x1_2b_f32.
 //
 // Workgroup tile 128 tokens x 128 sub-experts, 4 waves as 2 x 2, wave tile 64 x 64: lane l
 // feeds token row l and sub-expert row l of the wave tile; with the A-block broadcast
@@ -305,7 +149,166 @@ __global__ __launch_bounds__(256) void logits_mfma_kernel(const InT* __restrict_
 #undef LM_SSTORE
 }
 
+// Small problems (few 128 x 128 tiles): the per-logit chain of d dependent FMAs is what takes
+// the time, so the tile per wave is made as small as the matrix cores allow.
+// v_mfma_f32_4x4x1_16b_f32 performs 16 independent 4 x 4 rank-1 updates in 2 passes (8 cycles):
+// block b takes its 4 A values from lanes 4b..4b+3 and its 4 B values from the same lanes, and
+// lane 4b + j holds column j of block b, rows 0..3 in its 4 accumulator registers.  Again one
+// binary32 FMA per logit and k.  With block b = (p, q) multiplying tokens 4p..4p+3 by
+// sub-experts 4q..4q+3 (lane 4b + i feeds token 4p + i and sub-expert 4q + i) one instruction
+// covers 16 tokens x 16 sub-experts.  A dependent chain of these instructions issues only
+// every 44 to 64 cycles, so where the problem has enough work a wave keeps four chains going:
+// NSUB x NSUB such sub-tiles per wave (NSUB = 2: 32 x 32 per wave, 64 x 64 per workgroup of
+// 2 x 2 waves; NSUB = 1: 16 x 16 and 32 x 32, four times as many waves for the smallest
+// problems).
+// Operands are widened to fp32 once, when a slab of 32 k is stored to LDS (rows of 128 bytes
+// + 16 of padding: conflict-free 16-byte reads), so the inner loop is LDS reads and MFMAs only.
+// Global loads run PF slabs ahead in registers; LDS holds two slabs; one barrier per slab.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+constexpr int L4_ROWB = 144, L4_KB = 32;
+
+template <typename InT, int NSUB>
+__global__ __launch_bounds__(256) void logits_mfma4_kernel(const InT* __restrict__ x,
+                                                           const InT* __restrict__ w,
+                                                           const float* __restrict__ bias,
+                                                           float* __restrict__ logits,
+                                                           int32_t* __restrict__ hdr, int T, int d,
+                                                           int E) {
+  constexpr int ROW_GB = L4_KB * sizeof(InT);      // global bytes per row and slab: 64 or 128
+  constexpr int CPR = ROW_GB / 16;                  // 16-byte chunks per row: 4 or 8
+  constexpr int BT = 32 * NSUB;                     // tokens (and sub-experts) per workgroup
+  constexpr int L4_ROWS = 2 * BT;                   // LDS rows: BT tokens, then BT sub-experts
+  constexpr int CH = L4_ROWS * CPR / 256;           // chunks per thread and slab: 1, 2 or 4
+  constexpr int PF = CH >= 4 ? 4 : 8;               // slabs in flight
+  __shared__ __align__(16) unsigned char sm[2][L4_ROWS * L4_ROWB];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int wy = wv >> 1, wx = wv & 1;
+  if (blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) hdr[HDR_FLAGS] = 0;
+  const int m0 = blockIdx.y * BT, n0 = blockIdx.x * BT;
+
+  // loader: chunk id c = tid + 256 j -> row c / CPR, 16-byte piece c % CPR
+  const unsigned char* src[CH];
+  int dst[CH];
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const int c = tid + 256 * j, row = c / CPR, pc = c % CPR;
+    const InT* base = row < BT ? x + (size_t)min(m0 + row, T - 1) * d
+                               : w + (size_t)min(n0 + row - BT, E - 1) * d;
+    src[j] = reinterpret_cast<const unsigned char*>(base) + pc * 16;
+    dst[j] = row * L4_ROWB + pc * (sizeof(InT) == 2 ? 32 : 16);
+  }
+  auto sstore = [&](int buf, int j, uint4 v) {  // widen to fp32 (exact) and store
+    unsigned char* o = &sm[buf][dst[j]];
+    if (sizeof(InT) == 2) {
+      const uint4 lo = {v.x << 16, v.x & 0xffff0000u, v.y << 16, v.y & 0xffff0000u};
+      const uint4 hi = {v.z << 16, v.z & 0xffff0000u, v.w << 16, v.w & 0xffff0000u};
+      *reinterpret_cast<uint4*>(o) = lo;
+      *reinterpret_cast<uint4*>(o + 16) = hi;
+    } else {
+      *reinterpret_cast<uint4*>(o) = v;
+    }
+  };
+
+  const int blk = lane >> 2, li = lane & 3, p = blk >> 2, q = blk & 3;
+  const int a_off = (wy * 16 * NSUB + 4 * p + li) * L4_ROWB;
+  const int b_off = (BT + wx * 16 * NSUB + 4 * q + li) * L4_ROWB;
+
+  const int ns = d / L4_KB;  // d % 64 == 0
+  uint4 pre[PF][CH];
+#pragma unroll
+  for (int i = 0; i < PF; ++i)
+#pragma unroll
+    for (int j = 0; j < CH; ++j)
+      pre[i][j] = *reinterpret_cast<const uint4*>(src[j] + (size_t)(i < ns ? i : 0) * ROW_GB);
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    sstore(0, j, pre[0][j]);
+    pre[0][j] = *reinterpret_cast<const uint4*>(src[j] + (size_t)(PF < ns ? PF : 0) * ROW_GB);
+  }
+  __syncthreads();
+
+  f32x4_t acc[NSUB][NSUB];
+#pragma unroll
+  for (int ia = 0; ia < NSUB; ++ia)
+#pragma unroll
+    for (int ib = 0; ib < NSUB; ++ib) acc[ia][ib] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+  for (int s0 = 0; s0 < ns; s0 += PF) {
+#pragma unroll
+    for (int i = 0; i < PF; ++i) {  // slab s0 + i; s0 is a multiple of PF: ring slot and parity are static
+      const int sl = s0 + i;
+      if (sl < ns) {
+        const int nx = (i + 1) % PF, par = i & 1;
+        if (sl + 1 < ns) {
+#pragma unroll
+          for (int j = 0; j < CH; ++j) {
+            sstore(par ^ 1, j, pre[nx][j]);
+            pre[nx][j] = *reinterpret_cast<const uint4*>(
+                src[j] + (size_t)(sl + 1 + PF < ns ? sl + 1 + PF : 0) * ROW_GB);
+          }
+        }
+        const unsigned char* sa = &sm[par][a_off];
+        const unsigned char* sb = &sm[par][b_off];
+#pragma unroll
+        for (int g = 0; g < L4_KB / 4; ++g) {  // 4 k per 16-byte read, ascending k
+          f32x4_t fa[NSUB], fb[NSUB];
+#pragma unroll
+          for (int h = 0; h < NSUB; ++h) {
+            fa[h] = *reinterpret_cast<const f32x4_t*>(sa + h * 16 * L4_ROWB + g * 16);
+            fb[h] = *reinterpret_cast<const f32x4_t*>(sb + h * 16 * L4_ROWB + g * 16);
+          }
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int ia = 0; ia < NSUB; ++ia)
+#pragma unroll
+              for (int ib = 0; ib < NSUB; ++ib)
+                acc[ia][ib] = __builtin_amdgcn_mfma_f32_4x4x1f32(fa[ia][kk], fb[ib][kk], acc[ia][ib], 0, 0, 0);
+        }
+        // barrier that waits for this wave's LDS traffic only: __syncthreads() would also wait
+        // for the global loads just issued and expose their latency in every slab
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+    }
+  }
+
+#pragma unroll
+  for (int ia = 0; ia < NSUB; ++ia)
+#pragma unroll
+    for (int ib = 0; ib < NSUB; ++ib) {
+      const int col = n0 + wx * 16 * NSUB + ib * 16 + 4 * q + li;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int row = m0 + wy * 16 * NSUB + ia * 16 + 4 * p + v;
+        if (row < T && col < E) {
+          float r = acc[ia][ib][v];
+          if (bias != nullptr) r = r + bias[col];
+          logits[(size_t)row * E + col] = r;
+        }
+      }
+    }
+}
+
 __global__ void clear_flags_kernel(int32_t* hdr) { hdr[HDR_FLAGS] = 0; }
+
+// 128 x 128 tiles when they fill the chip; else the small-tile kernel, with four chains per
+// wave when that still gives every SIMD a wave.
+template <typename InT>
+static void launch_logits_t(const InT* x, const InT* w, const float* bias, float* logits,
+                            int32_t* hdr, int T, int d, int E, hipStream_t s) {
+  const long cus = num_cus();
+  if ((long)cdiv(E, 128) * cdiv(T, 128) >= cus + cus / 2)
+    logits_mfma_kernel<InT><<<dim3(cdiv(E, 128), cdiv(T, 128)), 256, 0, s>>>(x, w, bias, logits, hdr,
+                                                                             T, d, E);
+  else if ((long)cdiv(E, 64) * cdiv(T, 64) >= cus)
+    logits_mfma4_kernel<InT, 2><<<dim3(cdiv(E, 64), cdiv(T, 64)), 256, 0, s>>>(x, w, bias, logits,
+                                                                               hdr, T, d, E);
+  else
+    logits_mfma4_kernel<InT, 1><<<dim3(cdiv(E, 32), cdiv(T, 32)), 256, 0, s>>>(x, w, bias, logits,
+                                                                               hdr, T, d, E);
+}
 
 hipError_t launch_logits(int dtype, const void* x, const void* w, const float* bias, float* logits,
                          int32_t* hdr, int T, int d, int E, hipStream_t s) {
@@ -313,33 +316,10 @@ hipError_t launch_logits(int dtype, const void* x, const void* w, const float* b
     clear_flags_kernel<<<1, 1, 0, s>>>(hdr);
     return hipGetLastError();
   }
-  // Largest tile that still gives every CU work: the per-logit chains are long (d dependent
-  // FMAs), so with few sub-experts or tokens small tiles spread them over more waves.
-#define MP_LOGITS(BM_, BN_, TM_, TN_)                                                        \
-  do {                                                                                       \
-    dim3 grid(cdiv(E, BN_), cdiv(T, BM_));                                                   \
-    if (dtype == 0)                                                                          \
-      logits_kernel<float, BM_, BN_, TM_, TN_><<<grid, 256, 0, s>>>(                         \
-          (const float*)x, (const float*)w, bias, logits, hdr, T, d, E);                     \
-    else                                                                                     \
-      logits_kernel<uint16_t, BM_, BN_, TM_, TN_><<<grid, 256, 0, s>>>(                      \
-          (const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E);               \
-  } while (0)
-  const long cus = num_cus();
-  if ((long)cdiv(E, 128) * cdiv(T, 128) >= cus + cus / 2) {
-    dim3 grid(cdiv(E, 128), cdiv(T, 128));
-    if (dtype == 0)
-      logits_mfma_kernel<float><<<grid, 256, 0, s>>>((const float*)x, (const float*)w, bias,
-                                                     logits, hdr, T, d, E);
-    else
-      logits_mfma_kernel<uint16_t><<<grid, 256, 0, s>>>((const uint16_t*)x, (const uint16_t*)w,
-                                                        bias, logits, hdr, T, d, E);
-  }
-  else if ((long)cdiv(E, 64) * cdiv(T, 64) >= cus)
-    MP_LOGITS(64, 64, 4, 4);
+  if (dtype == 0)
+    launch_logits_t((const float*)x, (const float*)w, bias, logits, hdr, T, d, E, s);
   else
-    MP_LOGITS(32, 32, 2, 2);
-#undef MP_LOGITS
+    launch_logits_t((const uint16_t*)x, (const uint16_t*)w, bias, logits, hdr, T, d, E, s);
   return hipGetLastError();
 }
 
