@@ -111,11 +111,13 @@ def test_wide_router_and_large_k():
 
 
 @pytest.mark.parametrize("scale", [1.0, 1e-19])
-def test_matrix_core_logits_are_the_same_chain(scale):
-    # large T x E takes the matrix-core logits kernel (one fused multiply-add per k and
-    # instruction); it must reproduce the oracle's binary32 chain bit for bit, ragged edges
+@pytest.mark.parametrize("T,E", [(6200, 1000), (2100, 500), (300, 100)])
+def test_matrix_core_logits_are_the_same_chain(T, E, scale):
+    # the three logits kernels (128 x 128 tiles of 32x32x1 MFMAs; 64 x 64 and 32 x 32 tiles of
+    # 4x4x1 MFMAs, picked by problem size) each issue one fused multiply-add per k and
+    # instruction; each must reproduce the oracle's binary32 chain bit for bit, ragged edges
     # and subnormal partial sums (scale 1e-19: products ~1e-40) included
-    T, E, d = 6200, 1000, 192
+    d = 192
     rng = np.random.default_rng(11)
     wl = W.make_workload("wide", dtype="f32", d=d, n_experts=E, n_sub=1, inter_sub=32,
                          req_tokens=[T], req_k=[5], k_max=5, seed=11, w_std=0.05,
