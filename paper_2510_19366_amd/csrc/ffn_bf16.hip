@@ -498,7 +498,7 @@ __device__ __forceinline__ void wait_steady(int extra) {
     wait_copies<BASE>();
 }
 
-template <int BN, class Op>
+template <int BN, class Op, bool PP>
 __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restrict__ tiles,
                                               int32_t* __restrict__ hdr, int K, int n_tiles_n,
                                               int dyn_word) {
@@ -615,77 +615,43 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
     asm volatile("" ::: "memory");
 
     f32x16 acc[NB][2];
-  #pragma unroll
+#pragma unroll
     for (int nb = 0; nb < NB; ++nb)
-  #pragma unroll
+#pragma unroll
       for (int mb = 0; mb < 2; ++mb)
-  #pragma unroll
+#pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
     int mb_on = (cur.rows - wm * 64 + 31) / 32;
     mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
 
-    Frag f0, f1;
-    read_frags(0, 0, f0);
-    int c_stage = 0, c_item = 0, c_slot = 0;
-    int st_credit = 0, st_count = 0;  // iterations left in which st_count stores may be pending
-    for (int q = 0; q < total; ++q) {
-      const int n_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
-      // Stage q + 1 has landed once at most the operations issued after it are pending: the
-      // copies of the NS - 3 younger stages and, for NS - 2 iterations after an epilogue, that
-      // epilogue's stores (vector memory operations retire in issue order, loads and stores
-      // alike; counting the stores keeps the ring from draining behind every output tile).
-      if (p - q - 2 >= NS - 3) {
-        const int extra = st_credit > 0 ? st_count : 0;
-        if (nbd == 2) wait_steady<(NS - 3) * 4, Op::STORES_PER_MB>(extra);
-        else wait_steady<(NS - 3) * 3, Op::STORES_PER_MB>(extra);
-      } else {
-        wait_copies<0>();
-      }
-      st_credit = st_credit > 0 ? st_credit - 1 : 0;
-      __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
-      asm volatile("" ::: "memory");
-      if (p < total) {
-        if (p_stage == nst) {  // the producer enters the next item
-          p_stage = 0;
-          ++p_item;
-          producer_rows(nxt, p_item & 1);
-        }
-        issue_stage(p_slot, p_stage * SK);
-        ++p;
-        ++p_stage;
-        p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
-      }
-      // ---- MFMAs of stage q; the first fragments of stage q + 1 are fetched in between.
-      // A wave whose 64 slot rows are all beyond the tile's rows skips the MFMAs (the tile
-      // takes as long as its fullest wave, so finer skipping would buy nothing).
-      read_frags(c_slot, 1, f1);
-      if (mb_on > 0) {
-  #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-  #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.w[nb], f0.t[mb], acc[nb][mb], 0, 0, 0);
-      }
-      if (q + 1 < total) read_frags(n_slot, 0, f0);
-      if (mb_on > 0) {
-  #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-  #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.w[nb], f1.t[mb], acc[nb][mb], 0, 0, 0);
-      }
-      c_slot = n_slot;
-      if (++c_stage == nst) {  // the item is complete
+    if constexpr (PP) {
+      // ---- main loop.  The two wave groups (waves 0-3 and 4-7: one wave of each per SIMD) run
+      // the same sequence, group 1 one phase behind group 0: while one wave of a SIMD issues the
+      // MFMAs of a stage, the other does everything else (the previous tile's epilogue, waiting
+      // for copies, reading fragments, issuing copies), so the matrix pipe is not left idle
+      // during that work.  Phases are separated by workgroup barriers; to shift group 1 it takes
+      // one extra barrier before the loop and group 0 one after it.
+      //   prepare(q): wait for this wave's copies of stage q + 1 (every wave did the same for
+      //               stage q one or two phases ago, with a barrier since: stage q is complete;
+      //               waiting before issuing more copies also measured faster than after);
+      //               read this wave's fragments of stage q into registers; issue this wave's
+      //               copies of stage q + NS - 1 into the slot of stage q - 1, which both groups
+      //               have finished reading (reads are complete before a wave's barrier).
+      //   multiply(q): the MFMAs of stage q from registers.
+      Frag f0, f1;  // the two K halves of one stage
+      int c_stage = 0, c_item = 0, c_slot = 0;
+      int st_credit = 0, st_count = 0;  // iterations left in which st_count stores may be pending
+      bool item_done = false;
+      auto finish_item = [&]() {
         op.epilogue(cur, acc, mb_on, epi_lds);
         st_count = uni(op.stores_issued(cur, mb_on, wm, wn));
         st_credit = NS - 2;
-  #pragma unroll
+#pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-  #pragma unroll
+#pragma unroll
           for (int mb = 0; mb < 2; ++mb)
-  #pragma unroll
+#pragma unroll
             for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
-        c_stage = 0;
         ++c_item;
         cur = nxt;
         mb_on = (cur.rows - wm * 64 + 31) / 32;
@@ -693,6 +659,148 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
         if (c_item + 1 < n_my) {
           load_sc(c_item + 1, nxt);
           fetch_pairs(nxt, (c_item + 1) & 1);
+        }
+        item_done = false;
+      };
+      const int grp = wv >> 2;
+      if (grp == 1) {
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      for (int q = 0; q < total; ++q) {
+        // ---- prepare(q)
+        if (item_done) finish_item();
+        // Stage q + 1 has landed once at most the operations issued after it are pending: the
+        // copies of the NS - 3 younger stages and, for NS - 2 iterations after an epilogue, that
+        // epilogue's stores (vector memory operations retire in issue order, loads and stores
+        // alike; counting the stores keeps the ring from draining behind every output tile).
+        if (q + 1 < total) {
+          if (p - q - 2 >= NS - 3) {
+            const int extra = st_credit > 0 ? st_count : 0;
+            if (nbd == 2) wait_steady<(NS - 3) * 4, Op::STORES_PER_MB>(extra);
+            else wait_steady<(NS - 3) * 3, Op::STORES_PER_MB>(extra);
+          } else {
+            wait_copies<0>();
+          }
+        }
+        st_credit = st_credit > 0 ? st_credit - 1 : 0;
+        read_frags(c_slot, 0, f0);
+        read_frags(c_slot, 1, f1);
+        if (p < total) {
+          if (p_stage == nst) {  // the producer enters the next item
+            p_stage = 0;
+            ++p_item;
+            producer_rows(nxt, p_item & 1);
+          }
+          issue_stage(p_slot, p_stage * SK);
+          ++p;
+          ++p_stage;
+          p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // fragments are in registers
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // ---- multiply(q).  A wave whose 64 slot rows are all beyond the tile's rows skips the
+        // MFMAs (the tile takes as long as its fullest wave, so finer skipping would buy nothing).
+        if (mb_on > 0) {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.w[nb], f0.t[mb], acc[nb][mb], 0, 0, 0);
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.w[nb], f1.t[mb], acc[nb][mb], 0, 0, 0);
+        }
+        c_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
+        if (++c_stage == nst) {  // the item is complete; its epilogue runs in the next prepare phase
+          c_stage = 0;
+          item_done = true;
+        }
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      if (item_done) finish_item();
+      if (grp == 0) {
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+    } else {
+      // ---- main loop, all waves in step (short K: the epilogues dominate and are better run
+      // by all waves at once).  One barrier per stage publishes stage q + 1 and frees the
+      // slot of stage q - 1; the first fragments of stage q + 1 are read between the MFMAs.
+      Frag f0, f1;
+      read_frags(0, 0, f0);
+      int c_stage = 0, c_item = 0, c_slot = 0;
+      int st_credit = 0, st_count = 0;  // iterations left in which st_count stores may be pending
+      for (int q = 0; q < total; ++q) {
+        const int n_slot = c_slot + 1 == NS ? 0 : c_slot + 1;
+        // Stage q + 1 has landed once at most the operations issued after it are pending: the
+        // copies of the NS - 3 younger stages and, for NS - 2 iterations after an epilogue, that
+        // epilogue's stores (vector memory operations retire in issue order, loads and stores
+        // alike; counting the stores keeps the ring from draining behind every output tile).
+        if (p - q - 2 >= NS - 3) {
+          const int extra = st_credit > 0 ? st_count : 0;
+          if (nbd == 2) wait_steady<(NS - 3) * 4, Op::STORES_PER_MB>(extra);
+          else wait_steady<(NS - 3) * 3, Op::STORES_PER_MB>(extra);
+        } else {
+          wait_copies<0>();
+        }
+        st_credit = st_credit > 0 ? st_credit - 1 : 0;
+        __builtin_amdgcn_s_barrier();  // publishes stage q + 1, frees the slot of stage q - 1
+        asm volatile("" ::: "memory");
+        if (p < total) {
+          if (p_stage == nst) {  // the producer enters the next item
+            p_stage = 0;
+            ++p_item;
+            producer_rows(nxt, p_item & 1);
+          }
+          issue_stage(p_slot, p_stage * SK);
+          ++p;
+          ++p_stage;
+          p_slot = p_slot + 1 == NS ? 0 : p_slot + 1;
+        }
+        // ---- MFMAs of stage q; the first fragments of stage q + 1 are fetched in between.
+        // A wave whose 64 slot rows are all beyond the tile's rows skips the MFMAs (the tile
+        // takes as long as its fullest wave, so finer skipping would buy nothing).
+        read_frags(c_slot, 1, f1);
+        if (mb_on > 0) {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f0.w[nb], f0.t[mb], acc[nb][mb], 0, 0, 0);
+        }
+        if (q + 1 < total) read_frags(n_slot, 0, f0);
+        if (mb_on > 0) {
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f1.w[nb], f1.t[mb], acc[nb][mb], 0, 0, 0);
+        }
+        c_slot = n_slot;
+        if (++c_stage == nst) {  // the item is complete
+          op.epilogue(cur, acc, mb_on, epi_lds);
+          st_count = uni(op.stores_issued(cur, mb_on, wm, wn));
+          st_credit = NS - 2;
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+          c_stage = 0;
+          ++c_item;
+          cur = nxt;
+          mb_on = (cur.rows - wm * 64 + 31) / 32;
+          mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+          if (c_item + 1 < n_my) {
+            load_sc(c_item + 1, nxt);
+            fetch_pairs(nxt, (c_item + 1) & 1);
+          }
         }
       }
     }
@@ -709,19 +817,19 @@ __device__ __forceinline__ void run_items_dma(const Op& op, const MTile* __restr
   }
 }
 
-template <int BN>
+template <int BN, bool PP>
 __global__ __launch_bounds__(NT_) void gate_up_bf16_dma_kernel(GateUpOp<BN> op,
                                                                const MTile* __restrict__ tiles,
                                                                int32_t* __restrict__ hdr,
                                                                int n_tiles_n) {
-  run_items_dma<BN>(op, tiles, hdr, op.d, n_tiles_n, HDR_DYN_GATE_UP);
+  run_items_dma<BN, GateUpOp<BN>, PP>(op, tiles, hdr, op.d, n_tiles_n, HDR_DYN_GATE_UP);
 }
-template <int BN>
+template <int BN, bool PP>
 __global__ __launch_bounds__(NT_) void down_bf16_dma_kernel(DownOp<BN> op,
                                                             const MTile* __restrict__ tiles,
                                                             int32_t* __restrict__ hdr,
                                                             int n_tiles_n) {
-  run_items_dma<BN>(op, tiles, hdr, op.Is, n_tiles_n, HDR_DYN_DOWN);
+  run_items_dma<BN, DownOp<BN>, PP>(op, tiles, hdr, op.Is, n_tiles_n, HDR_DYN_DOWN);
 }
 
 // ---------------------------------------------------------------- launchers
@@ -747,66 +855,64 @@ static int pick_bn(int n, int wide, int narrow) {
   return pn < pw ? narrow : wide;
 }
 
+template <auto Kern, class Op>
+static hipError_t launch_persistent(const Op& op, size_t lds_bytes, int grid, const MTile* tiles,
+                                    int32_t* hdr, int ntn, hipStream_t s) {
+  hipError_t e = allow_lds<Kern>(lds_bytes);
+  if (e != hipSuccess) return e;
+  Kern<<<grid, NT_, lds_bytes, s>>>(op, tiles, hdr, ntn);
+  return hipGetLastError();
+}
+
+// Items with at least this many K stages run the two-group schedule; with fewer, the epilogues
+// dominate and the in-step schedule is faster (measured at K = 192: 6 stages per item).
+constexpr int PP_MIN_STAGES = 12;
+
+template <int BN>
+static hipError_t launch_gate_up_bn(const GateUpOp<BN>& op, int max_mtiles, const MTile* tiles,
+                                    int32_t* hdr, hipStream_t s) {
+  using RG = Ring<BN, true>;
+  const int ntn = cdiv(op.Is, BN / 2);
+  const int grid = persistent_grid((long)max_mtiles * ntn, 1);
+  const int nst = op.d / SK;
+  // the ring needs the next tile's slot-list entries one item ahead, published by a barrier
+  // before any wave uses them: K/32 >= 2 D stages per item
+  if (nst >= 2 * RG::D && nst >= PP_MIN_STAGES)
+    return launch_persistent<gate_up_bf16_dma_kernel<BN, true>>(op, RG::LDS_BYTES, grid, tiles, hdr, ntn, s);
+  if (nst >= 2 * RG::D)
+    return launch_persistent<gate_up_bf16_dma_kernel<BN, false>>(op, RG::LDS_BYTES, grid, tiles, hdr, ntn, s);
+  return launch_persistent<gate_up_bf16_kernel<BN>>(op, Tile<BN>::LDS_BYTES, grid, tiles, hdr, ntn, s);
+}
+
 hipError_t launch_gate_up_bf16(const uint16_t* x, const uint16_t* w_gu, const int32_t* sorted_pair,
                                const MTile* tiles, int32_t* hdr, uint16_t* h, int T, int d,
                                int Is, int k_max, int max_mtiles, hipStream_t s) {
-  hipError_t e;
-  // the ring needs the next tile's slot-list entries one item ahead: K/32 >= 2 D - 1 stages
-  if (pick_bn(Is, 128, 96) == 128) {
-    GateUpOp<256> op{x, w_gu, sorted_pair, h, T, d, Is, k_max};
-    const int ntn = cdiv(Is, 128);
-    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (d / SK >= 2 * Ring<256, true>::D - 1) {
-      if ((e = allow_lds<gate_up_bf16_dma_kernel<256>>(Ring<256, true>::LDS_BYTES)) != hipSuccess) return e;
-      gate_up_bf16_dma_kernel<256><<<grid, NT_, Ring<256, true>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    } else {
-      if ((e = allow_lds<gate_up_bf16_kernel<256>>(Tile<256>::LDS_BYTES)) != hipSuccess) return e;
-      gate_up_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    }
-  } else {
-    GateUpOp<192> op{x, w_gu, sorted_pair, h, T, d, Is, k_max};
-    const int ntn = cdiv(Is, 96);
-    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (d / SK >= 2 * Ring<192, true>::D - 1) {
-      if ((e = allow_lds<gate_up_bf16_dma_kernel<192>>(Ring<192, true>::LDS_BYTES)) != hipSuccess) return e;
-      gate_up_bf16_dma_kernel<192><<<grid, NT_, Ring<192, true>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    } else {
-      if ((e = allow_lds<gate_up_bf16_kernel<192>>(Tile<192>::LDS_BYTES)) != hipSuccess) return e;
-      gate_up_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    }
-  }
-  return hipGetLastError();
+  if (pick_bn(Is, 128, 96) == 128)
+    return launch_gate_up_bn(GateUpOp<256>{x, w_gu, sorted_pair, h, T, d, Is, k_max}, max_mtiles, tiles, hdr, s);
+  return launch_gate_up_bn(GateUpOp<192>{x, w_gu, sorted_pair, h, T, d, Is, k_max}, max_mtiles, tiles, hdr, s);
+}
+
+template <int BN>
+static hipError_t launch_down_bn(const DownOp<BN>& op, int max_mtiles, const MTile* tiles,
+                                 int32_t* hdr, hipStream_t s) {
+  using RG = Ring<BN, false>;
+  const int ntn = cdiv(op.d, BN);
+  const int grid = persistent_grid((long)max_mtiles * ntn, 1);
+  const int nst = op.Is / SK;
+  // the ring keeps D stages in flight inside one item or the next: K/32 >= NS stages per item
+  if (nst >= RG::NS && nst >= PP_MIN_STAGES)
+    return launch_persistent<down_bf16_dma_kernel<BN, true>>(op, RG::LDS_BYTES, grid, tiles, hdr, ntn, s);
+  if (nst >= RG::NS)
+    return launch_persistent<down_bf16_dma_kernel<BN, false>>(op, RG::LDS_BYTES, grid, tiles, hdr, ntn, s);
+  return launch_persistent<down_bf16_kernel<BN>>(op, Tile<BN>::LDS_BYTES, grid, tiles, hdr, ntn, s);
 }
 
 hipError_t launch_down_bf16(const uint16_t* h, const uint16_t* w_dn, const MTile* tiles,
                             int32_t* hdr, uint16_t* y, int d, int Is, int max_mtiles,
                             hipStream_t s) {
-  hipError_t e;
-  // the ring keeps D stages in flight inside one item or the next: K/32 >= D stages per item
-  if (pick_bn(d, 256, 192) == 256) {
-    DownOp<256> op{h, w_dn, y, d, Is};
-    const int ntn = cdiv(d, 256);
-    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (Is / SK >= Ring<256, false>::NS) {
-      if ((e = allow_lds<down_bf16_dma_kernel<256>>(Ring<256, false>::LDS_BYTES)) != hipSuccess) return e;
-      down_bf16_dma_kernel<256><<<grid, NT_, Ring<256, false>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    } else {
-      if ((e = allow_lds<down_bf16_kernel<256>>(Tile<256>::LDS_BYTES)) != hipSuccess) return e;
-      down_bf16_kernel<256><<<grid, NT_, Tile<256>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    }
-  } else {
-    DownOp<192> op{h, w_dn, y, d, Is};
-    const int ntn = cdiv(d, 192);
-    const int grid = persistent_grid((long)max_mtiles * ntn, 1);
-    if (Is / SK >= Ring<192, false>::NS) {
-      if ((e = allow_lds<down_bf16_dma_kernel<192>>(Ring<192, false>::LDS_BYTES)) != hipSuccess) return e;
-      down_bf16_dma_kernel<192><<<grid, NT_, Ring<192, false>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    } else {
-      if ((e = allow_lds<down_bf16_kernel<192>>(Tile<192>::LDS_BYTES)) != hipSuccess) return e;
-      down_bf16_kernel<192><<<grid, NT_, Tile<192>::LDS_BYTES, s>>>(op, tiles, hdr, ntn);
-    }
-  }
-  return hipGetLastError();
+  if (pick_bn(d, 256, 192) == 256)
+    return launch_down_bn(DownOp<256>{h, w_dn, y, d, Is}, max_mtiles, tiles, hdr, s);
+  return launch_down_bn(DownOp<192>{h, w_dn, y, d, Is}, max_mtiles, tiles, hdr, s);
 }
 
 }  // namespace mp

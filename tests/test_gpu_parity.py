@@ -52,6 +52,10 @@ def test_config1_tiny_f32_stage_by_stage():
     dict(T=2100, d=512, N=3, S=4, Is=352, k_max=7),
     dict(T=600, d=256, N=2, S=1, Is=1024, k_max=2),
     dict(T=500, d=128, N=4, S=2, Is=128, k_max=4),
+    # K of 12 or more stages: the two-group schedule, with 192-wide tiles (the cases above reach
+    # it with 256-wide tiles, and the in-step ring schedule with both widths)
+    dict(T=800, d=384, N=4, S=2, Is=192, k_max=4),
+    dict(T=600, d=192, N=2, S=2, Is=416, k_max=3),
 ])
 def test_small_cases_full_oracle(dtype, case):
     rng = np.random.default_rng(case["T"])
