@@ -21,7 +21,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for that workload.
-TRAFFIC_BYTES = {"c3_fine_128x4": 2.54e9}   # gate-up kernel: 2.418 GB fetched + 0.122 GB written
+TRAFFIC_BYTES = {"c3_fine_128x4": 2.27e9}   # gate-up kernel: 2.143 GB fetched + 0.122 GB written
 
 
 def main():
