@@ -14,6 +14,8 @@
  *   - Gate-weighted sum of the selected sub-expert outputs: Sec. 3.2.2 (the
  *     routed-output expression of the proxy-gating paragraph; the linear gate
  *     uses the same sum with one weight per sub-expert).
+ *   - Training-free proxy gate (original router, gate-neuron scores, per-expert
+ *     top-kappa): Sec. 3.2.2 ("Training-Free Proxy Gating"); at the end of this file.
  *
  * Precision.  Router logits decide integers (which sub-experts are chosen), so
  * they are computed in the precision the device uses for that decision: one
@@ -252,6 +254,95 @@ ORACLE_API int oracle_layer_tokens(int n_sel, const int32_t *tokens, int d, int 
             if (w_out) memcpy(w_out + (size_t)i * k_max, w, sizeof(double) * (size_t)k_max);
         }
         free(l); free(id); free(w); free(h); free(y);
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * Training-free proxy gating ("complex gate"), Sec. 3.2.2.
+ *
+ * The pre-existing router scores the N original experts and takes its native
+ * top m (oracle_logits / oracle_select / oracle_weights with E = N, k = m).
+ * For a token routed to original expert e, sub-expert n of e is scored by the
+ * mean absolute activation of its r gate neurons,
+ *     s_n(x) = (1/r) sum_{c in G_n} | SiLU(x . Wg[c,:]) * (x . Wu[c,:]) |,
+ * and among the S sub-experts of the expert ranked j the top kappa_j by s are
+ * executed, where (kappa_1..kappa_m) is the configured split of the token's
+ * budget k.  Every selected sub-expert inherits the weight of its expert.
+ *
+ * w_proxy holds, per original expert, the gate rows of its S*r gate neurons
+ * (sub-expert-major: neuron c of sub-expert n at row n*r + c) followed by
+ * their up rows: [N][2*S*r][d].  Scores are binary64.
+ * ------------------------------------------------------------------------ */
+ORACLE_API int oracle_proxy_scores(int T, int d, int S, int r, int m, const float *x,
+                                   const float *w_proxy, const int32_t *ids0, double *scores)
+{
+    const int R = S * r;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        const float *xr = x + (size_t)t * d;
+        for (int j = 0; j < m; ++j) {
+            int e = ids0[(size_t)t * m + j];
+            double *s = scores + ((size_t)t * m + j) * S;
+            for (int n = 0; n < S; ++n) s[n] = 0.0;
+            if (e < 0) continue;
+            const float *wg = w_proxy + (size_t)e * 2 * R * d;
+            const float *wu = wg + (size_t)R * d;
+            for (int n = 0; n < S; ++n) {
+                double sum = 0.0;
+                for (int c = 0; c < r; ++c) {
+                    const float *g = wg + (size_t)(n * r + c) * d;
+                    const float *u = wu + (size_t)(n * r + c) * d;
+                    double a = 0.0, b = 0.0;
+                    for (int i = 0; i < d; ++i) {
+                        a += (double)xr[i] * (double)g[i];
+                        b += (double)xr[i] * (double)u[i];
+                    }
+                    sum += fabs(a / (1.0 + exp(-a)) * b);
+                }
+                s[n] = sum / (double)r;
+            }
+        }
+    }
+    return 0;
+}
+
+/* Per expert rank j: the kappa[k_t][j] best-scored sub-experts of expert
+ * ids0[t,j] (score descending, equal scores to the smaller index), appended in
+ * rank order; flat sub-expert id e*S + n; weight w0[t,j].  kappa is
+ * [(k_cap+1)][m]; budgets are clamped to [0, min(k_max, k_cap)]. */
+ORACLE_API int oracle_proxy_select(int T, int S, int m, int k_max, int k_cap,
+                                   const double *scores, const int32_t *ids0, const double *w0,
+                                   const int32_t *k_tok, const int32_t *kappa, int32_t *ids,
+                                   double *w)
+{
+    int rc = 0;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) {
+        int kt = clamp_k(k_tok[t], k_max < k_cap ? k_max : k_cap);
+        int32_t *o = ids + (size_t)t * k_max;
+        double *ow = w + (size_t)t * k_max;
+        for (int i = 0; i < k_max; ++i) { o[i] = -1; ow[i] = 0.0; }
+        int pos = 0;
+        for (int j = 0; j < m; ++j) {
+            int kap = kappa[(size_t)kt * m + j];
+            int e = ids0[(size_t)t * m + j];
+            if (kap < 0 || kap > S) { rc = -1; continue; }
+            if (e < 0) continue;
+            const double *s = scores + ((size_t)t * m + j) * S;
+            char taken[64] = {0};
+            for (int i = 0; i < kap && pos < k_max; ++i) {
+                int best = -1;
+                for (int n = 0; n < S && n < 64; ++n) {
+                    if (taken[n]) continue;
+                    if (best < 0 || s[n] > s[best]) best = n;
+                }
+                taken[best] = 1;
+                o[pos] = e * S + best;
+                ow[pos] = w0[(size_t)t * m + j];
+                ++pos;
+            }
+        }
     }
     return rc;
 }

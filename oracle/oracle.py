@@ -185,3 +185,50 @@ def layer_of(wl, **kw):
     """Convenience: run ``layer`` on a workloads.Workload-shaped object."""
     return layer(wl.x, wl.w_router, wl.router_bias, wl.k_tok, wl.w_gate_up, wl.w_down,
                  wl.k_max, wl.renormalize, wl.routed_scale, **kw)
+
+
+# ---------------------------------------------------------------- proxy gating (Sec. 3.2.2)
+def proxy_scores(x, w_proxy, ids0, S, r):
+    """scores [T, m, S] float64: mean |activation| of the r gate neurons of every
+    sub-expert of the experts in ids0 [T, m].  w_proxy is [N, 2*S*r, d]."""
+    x, w_proxy, ids0 = _f32(x), _f32(w_proxy), _i32(ids0)
+    T, d = x.shape
+    m = ids0.shape[1]
+    assert w_proxy.shape[1] == 2 * S * r and w_proxy.shape[2] == d
+    s = np.empty((T, m, S), np.float64)
+    rc = lib().oracle_proxy_scores(T, d, S, r, m, _p(x, C.c_float), _p(w_proxy, C.c_float),
+                                   _p(ids0, C.c_int32), _p(s, C.c_double))
+    assert rc == 0
+    return s
+
+
+def proxy_select(scores, ids0, w0, k_tok, kappa, k_max):
+    """ids [T, k_max] (flat sub-expert ids, -1 padded) and weights [T, k_max] float64."""
+    scores = np.ascontiguousarray(scores, np.float64)
+    w0 = np.ascontiguousarray(w0, np.float64)
+    ids0, k_tok, kappa = _i32(ids0), _i32(k_tok), _i32(kappa)
+    T, m, S = scores.shape
+    assert S <= 64 and kappa.shape[1] == m
+    ids = np.empty((T, k_max), np.int32)
+    w = np.empty((T, k_max), np.float64)
+    rc = lib().oracle_proxy_select(T, S, m, k_max, kappa.shape[0] - 1, _p(scores, C.c_double),
+                                   _p(ids0, C.c_int32), _p(w0, C.c_double), _p(k_tok, C.c_int32),
+                                   _p(kappa, C.c_int32), _p(ids, C.c_int32), _p(w, C.c_double))
+    if rc:
+        raise ValueError("allocation table entry outside [0, S]")
+    return ids, w
+
+
+def route_proxy(x, w_router0, bias0, w_proxy, k_tok, kappa, S, r, m, k_max, renormalize,
+                routed_scale, return_all=False):
+    """The whole proxy-gate route stage: (ids, w) over the N*S sub-experts."""
+    T = x.shape[0]
+    lg0 = logits(x, w_router0, bias0)
+    k_m = np.full(T, m, np.int32)
+    ids0 = select(lg0, k_m, m)
+    w0 = weights(lg0, ids0, k_m, renormalize, routed_scale)
+    sc = proxy_scores(x, w_proxy, ids0, S, r)
+    ids, w = proxy_select(sc, ids0, w0, k_tok, kappa, k_max)
+    if return_all:
+        return dict(logits0=lg0, ids0=ids0, w0=w0, scores=sc, ids=ids, w=w)
+    return ids, w

@@ -219,3 +219,48 @@ def split_workload(a: Workload, S: int) -> Workload:
                     w_router=repeat_router_rows(a.w_router, S), router_bias=bias,
                     w_gate_up=gu, w_down=dn, req_k=a.req_k * S, req_off=a.req_off,
                     k_tok=a.k_tok * S, meta=dict(a.meta))
+
+
+# ---------------------------------------------------------------- proxy gate inputs
+def default_kappa_table(m: int, S: int) -> np.ndarray:
+    """Allocation table of the proxy gate (Sec. 3.2.2): row k is (kappa_1..kappa_m) with
+    sum k and 0 <= kappa_j <= S, for every budget k in 0..m*S.  The paper leaves the split
+    to configuration; this one spreads the budget evenly and gives the remainder to the
+    experts the router ranked first."""
+    tab = np.zeros((m * S + 1, m), np.int32)
+    for k in range(m * S + 1):
+        base, rem = divmod(k, m)
+        tab[k] = base + (np.arange(m) < rem)
+    assert tab.max() <= S and np.array_equal(tab.sum(1), np.arange(m * S + 1))
+    return tab
+
+
+@dataclass
+class ProxyGate:
+    m: int                      # experts the original router selects
+    r: int                      # gate neurons per sub-expert
+    r_pad: int                  # S*r_pad is the padded row count per half of w_proxy (multiple of 32)
+    w_router0: np.ndarray       # [N, d] original router
+    bias0: Optional[np.ndarray]
+    gate_neurons: np.ndarray    # [N*S, r] neuron indices inside each sub-expert
+    w_proxy: np.ndarray         # [N, 2*S*r, d]   gate rows (sub-expert-major), then up rows
+    kappa: np.ndarray           # [(m*S)+1, m]
+
+
+def make_proxy_gate(whole: Workload, split: Workload, m: int, r: int, seed: int = 0) -> ProxyGate:
+    """Synthetic proxy-gate metadata for `split` = split_workload(whole, S): r gate neurons
+    drawn at random inside every sub-expert (the paper picks them by co-activation on
+    calibration data, which does not exist here), their gate/up rows gathered per original
+    expert, and the default allocation table."""
+    assert whole.n_sub == 1 and split.n_experts == whole.n_experts
+    N, S, Is, d = split.n_experts, split.n_sub, split.inter_sub, split.d
+    rng = np.random.default_rng(seed)
+    G = np.stack([np.sort(rng.choice(Is, size=r, replace=False)) for _ in range(N * S)]).astype(np.int32)
+    w_proxy = np.empty((N, 2 * S * r, d), np.float32)
+    for e in range(N):
+        for n in range(S):
+            g = e * S + n
+            w_proxy[e, n * r:(n + 1) * r] = split.w_gate_up[g, G[g]]
+            w_proxy[e, S * r + n * r:S * r + (n + 1) * r] = split.w_gate_up[g, Is + G[g]]
+    return ProxyGate(m=m, r=r, r_pad=r, w_router0=whole.w_router, bias0=whole.router_bias,
+                     gate_neurons=G, w_proxy=w_proxy, kappa=default_kappa_table(m, S))

@@ -395,3 +395,130 @@ def test_config1_recipe():
     assert abs(float(wl.w_router.std()) - 0.02) < 2e-3 and abs(float(wl.x.std()) - 1.0) < 2e-2
     b = W.round_to_bf16(np.array([1.00390625, 1.01171875, -3.0e38, 1e-40], np.float32))
     assert b.tolist()[:2] == [1.0, 1.015625]          # ties to even both ways
+
+
+# ----------------------------------------------------------------- proxy gate (Sec. 3.2.2)
+def proxy_fixture(seed=31, T=14, d=32, N=6, I=32, S=4, m=3, r=2, renorm=1):
+    base = W.make_workload("whole", dtype="f32", d=d, n_experts=N, n_sub=1, inter_sub=I,
+                           req_tokens=[T], req_k=[m], k_max=m, seed=seed, routed_scale=1.0,
+                           w_std=0.3, renormalize=renorm)
+    sp = W.split_workload(base, S)
+    pg = W.make_proxy_gate(base, sp, m=m, r=r, seed=seed + 1)
+    return base, sp, pg
+
+
+def proxy_layer(sp, pg, k_tok, routed_scale=1.0):
+    S = sp.n_sub
+    k_max = pg.m * S
+    ids, w = O.route_proxy(sp.x, pg.w_router0, pg.bias0, pg.w_proxy, k_tok, pg.kappa, S, pg.r,
+                           pg.m, k_max, sp.renormalize, routed_scale)
+    cnt, off, spair, slot = O.dispatch(ids, sp.E)
+    y = O.grouped_ffn(sp.x, sp.w_gate_up, sp.w_down, off, spair, k_max)
+    k_eff = (ids >= 0).sum(1).astype(np.int32)
+    return O.combine(y, slot, w, k_eff, sp.T), ids, w
+
+
+def test_proxy_scores_hand_computed():
+    # d = 2, one expert, two sub-experts with one gate neuron each
+    x = np.array([[1.0, 2.0]], np.float32)
+    w_proxy = np.array([[[0.5, 0.25], [-1.0, 0.0],        # gate rows of sub-experts 0, 1
+                         [2.0, 1.0], [1.0, 1.0]]], np.float32)   # their up rows
+    ids0 = np.array([[0]], np.int32)
+    s = O.proxy_scores(x, w_proxy, ids0, S=2, r=1)
+    s0 = abs(1.0 / (1.0 + math.exp(-1.0)) * 4.0)          # a = 1, u = 4
+    s1 = abs(-1.0 / (1.0 + math.exp(1.0)) * 3.0)          # a = -1, u = 3
+    np.testing.assert_allclose(s[0, 0], [s0, s1], rtol=1e-15)
+    kappa = np.array([[0], [1], [2]], np.int32)
+    ids, w = O.proxy_select(s, ids0, np.array([[0.7]]), np.array([1], np.int32), kappa, 2)
+    assert ids.tolist() == [[0, -1]] and w.tolist() == [[0.7, 0.0]]
+    ids, w = O.proxy_select(s, ids0, np.array([[0.7]]), np.array([2], np.int32), kappa, 2)
+    assert ids.tolist() == [[0, 1]] and w.tolist() == [[0.7, 0.7]]
+
+
+def test_proxy_scores_with_every_neuron_equal_mean_abs_activation():
+    # r = Is: the score is the mean |h_c| over the sub-expert, h from dense numpy code
+    base, sp, _ = proxy_fixture(seed=33, S=4, I=32)
+    S, Is, N, d = sp.n_sub, sp.inter_sub, sp.n_experts, sp.d
+    w_proxy = np.empty((N, 2 * S * Is, d), np.float32)
+    for e in range(N):
+        w_proxy[e, :S * Is] = base.w_gate_up[e, :S * Is]            # gate rows, neuron order
+        w_proxy[e, S * Is:] = base.w_gate_up[e, S * Is:]            # up rows
+    ids0 = np.tile(np.arange(N, dtype=np.int32), (sp.T, 1))
+    s = O.proxy_scores(sp.x, w_proxy, ids0, S=S, r=Is)
+    x64 = sp.x.astype(np.float64)
+    for e in range(N):
+        a = x64 @ base.w_gate_up[e, :S * Is].astype(np.float64).T
+        u = x64 @ base.w_gate_up[e, S * Is:].astype(np.float64).T
+        h = np.abs(a / (1.0 + np.exp(-a)) * u).reshape(sp.T, S, Is).mean(2)
+        np.testing.assert_allclose(s[:, e], h, rtol=1e-12)
+
+
+def test_proxy_select_brute_force_and_ties():
+    rng = np.random.default_rng(34)
+    T, m, S = 40, 3, 5
+    scores = rng.integers(0, 4, size=(T, m, S)).astype(np.float64)      # many exact ties
+    ids0 = np.stack([rng.permutation(7)[:m] for _ in range(T)]).astype(np.int32)
+    w0 = rng.random((T, m))
+    kappa = np.array([[a, b, k - a - b] for k in range(m * S + 1)
+                      for a, b in [(min(S, k), min(S, max(0, k - S)))]], np.int32)
+    k_tok = rng.integers(0, m * S + 1, size=T).astype(np.int32)
+    ids, w = O.proxy_select(scores, ids0, w0, k_tok, kappa, m * S)
+    for t in range(T):
+        pos = 0
+        for j in range(m):
+            kap = kappa[k_tok[t], j]
+            got = ids[t, pos:pos + kap]
+            assert np.all(got // S == ids0[t, j]) and np.all(w[t, pos:pos + kap] == w0[t, j])
+            sub = (got % S).tolist()
+            best = max(sum(scores[t, j, list(c)]) for c in itertools.combinations(range(S), kap))
+            assert sum(scores[t, j, sub]) == best                         # an optimal subset
+            # the unique order: score descending, equal scores by ascending index
+            assert sub == sorted(range(S), key=lambda n: (-scores[t, j, n], n))[:kap]
+            pos += kap
+        assert pos == k_tok[t] and np.all(ids[t, pos:] == -1) and np.all(w[t, pos:] == 0)
+
+
+@pytest.mark.parametrize("renorm", [0, 1])
+def test_proxy_full_allocation_reconstructs_the_original_layer(renorm):
+    # selecting all S sub-experts of every selected expert gives the undivided top-m MoE
+    base, sp, pg = proxy_fixture(seed=35, renorm=renorm)
+    k_tok = np.full(sp.T, pg.m * sp.n_sub, np.int32)
+    out, ids, w = proxy_layer(sp, pg, k_tok)
+    I = base.inter_sub
+    ref = standard_topk_moe64(base.x, base.w_router, base.w_gate_up[:, :I], base.w_gate_up[:, I:],
+                              base.w_down, pg.m, renorm, 1.0)
+    np.testing.assert_allclose(out, ref, rtol=5e-5, atol=1e-8)
+    for t in range(sp.T):
+        experts = ids[t] // sp.n_sub
+        assert sorted(ids[t].tolist()) == sorted(e * sp.n_sub + n for e in set(experts) for n in range(sp.n_sub))
+
+
+def test_proxy_partial_budgets_follow_the_allocation_table():
+    base, sp, pg = proxy_fixture(seed=36)
+    S, m = sp.n_sub, pg.m
+    rng = np.random.default_rng(36)
+    k_tok = rng.integers(0, m * S + 1, size=sp.T).astype(np.int32)
+    r = O.route_proxy(sp.x, pg.w_router0, pg.bias0, pg.w_proxy, k_tok, pg.kappa, S, pg.r, m, m * S,
+                      1, 1.0, return_all=True)
+    ids, w = r["ids"], r["w"]
+    np.testing.assert_allclose(r["w0"].sum(1), 1.0, rtol=1e-12)          # renormalised over the m experts
+    for t in range(sp.T):
+        valid = ids[t][ids[t] >= 0]
+        assert len(valid) == k_tok[t] == len(set(valid.tolist()))
+        for j in range(m):
+            mine = valid[valid // S == r["ids0"][t, j]]
+            assert len(mine) == pg.kappa[k_tok[t], j]
+            assert np.all(w[t][ids[t] // S == r["ids0"][t, j]][:len(mine)] == r["w0"][t, j])
+        # each token's output is the weighted sum of exactly those sub-experts
+    out, _, _ = proxy_layer(sp, pg, k_tok)
+    for t in (0, 5, 9):
+        ref = sum(w[t, i] * O.ffn_one(sp.x[t], sp.w_gate_up[ids[t, i]], sp.w_down[ids[t, i]])
+                  for i in range(k_tok[t])) if k_tok[t] else np.zeros(sp.d)
+        np.testing.assert_allclose(out[t], ref, rtol=1e-12, atol=1e-15)
+
+
+def test_default_kappa_table():
+    tab = W.default_kappa_table(8, 4)
+    assert tab.shape == (33, 8) and np.array_equal(tab.sum(1), np.arange(33)) and tab.max() == 4
+    assert tab[20].tolist() == [3, 3, 3, 3, 2, 2, 2, 2]
+    assert np.all(np.diff(tab, axis=1) <= 0)          # never more for a lower-ranked expert
