@@ -34,6 +34,10 @@ def main():
     ap.add_argument("--tokens", type=int, default=None, help="token count for the c5 sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--route", default="linear", choices=["linear", "proxy"],
+                    help="linear: the expanded linear gate (default, the headline); proxy: the "
+                         "training-free proxy gate on the 128-expert layer split in 4 (m = 8 "
+                         "original experts, r = 4 gate neurons), per-request budgets in [8, 32]")
     ap.add_argument("--graph", action="store_true",
                     help="additionally time the same steps replayed from one captured HIP graph "
                          "(reported as graph_ms_per_step; the headline numbers stay the eager ones)")
@@ -54,15 +58,31 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    wl = W.config(args.workload, T=args.tokens) if args.workload.startswith("c5") else W.config(args.workload)
+    if args.route == "proxy":
+        from paper_2510_19366_amd.compare_modes import request_budgets
+        whole = W.config("c5a_s1_k8", T=args.tokens)
+        wl = W.split_workload(whole, 4)
+        wl.name, wl.routed_scale = "c5b_s4_proxy_gate", 1.0
+        wl.req_k, wl.k_tok = request_budgets(wl.T, 64, 8, 32, seed=3)
+        pg = W.make_proxy_gate(whole, wl, m=8, r=4, seed=6)
+        del whole
+    else:
+        wl = W.config(args.workload, T=args.tokens) if args.workload.startswith("c5") else W.config(args.workload)
     dev = B.to_device(wl)
     shape = dev["shape"]
     ws = B.alloc_workspace(shape)
     out = torch.empty((wl.T, wl.d), dtype=B.act_dtype(shape), device="cuda")
 
-    def step():
-        B.moe_prism_layer(shape, dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"],
-                          dev["w_gate_up"], dev["w_down"], ws, out=out)
+    if args.route == "proxy":
+        pdev = B.proxy_to_device(pg, wl.dtype)
+
+        def step():
+            B.moe_prism_layer_proxy(shape, dev["x"], pdev, dev["k_tok"], dev["w_gate_up"],
+                                    dev["w_down"], ws, out=out)
+    else:
+        def step():
+            B.moe_prism_layer(shape, dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"],
+                              dev["w_gate_up"], dev["w_down"], ws, out=out)
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -90,7 +110,13 @@ def main():
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = wl.T / (ms_per_step * 1e-3)
-    kern_ms = {k: (v[0] / max(v[1], 1)) for k, v in kt.items()}
+    # average launch duration; with the proxy gate the route stage launches the logits, top-k,
+    # dispatch, tile and gate-up kernels a second time on small shapes, so there the figures
+    # are per-step sums
+    if args.route == "proxy":
+        kern_ms = {k: v[0] / args.steps for k, v in kt.items()}
+    else:
+        kern_ms = {k: (v[0] / max(v[1], 1)) for k, v in kt.items()}
     P, d, Is, E = wl.pairs, wl.d, wl.inter_sub, wl.E
 
     # dominant kernel: the gate-up GEMM (2/3 of the FFN FLOPs); algorithmic FLOPs = 4*d*Is per pair
@@ -121,7 +147,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "T": wl.T, "d": d, "n_experts": wl.n_experts,
                    "n_sub": wl.n_sub, "inter_sub": Is, "k_max": wl.k_max, "pairs": P,
-                   "requests": int(len(wl.req_k)), "k_mix": "per-request"},
+                   "requests": int(len(wl.req_k)), "k_mix": "per-request", "route": args.route},
         "ffn_mfma_util_pct": 100.0 * ffn_tflops / PEAK_BF16_TFLOPS,
         "ffn_tflops": ffn_tflops,
         "ffn_ms": ffn_ms,
@@ -148,7 +174,7 @@ def main():
         torch.cuda.synchronize()
         res["graph_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.route == "linear":
         from oracle import oracle as O
         x32, wr32 = wl.x, wl.w_router
         rng = np.random.default_rng(0)

@@ -150,6 +150,48 @@ MOE_PRISM_API int moe_prism_layer(const moe_prism_shape* shape, const void* x, c
                     const void* w_down, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Proxy-gate route mode (Sec. 3.2.2, "Training-Free Proxy Gating"): routing for a model
+ * refactored WITHOUT training a new gate.  The original router w_router0 [N, d] (+ bias0 [N]
+ * or NULL) scores the N original experts and its native top m are taken, ordered by logit,
+ * with weights w_j = softmax (renormalised over the m if shape->renormalize) x routed_scale.
+ * For the expert ranked j its S = shape->n_sub sub-experts are scored by the mean absolute
+ * SwiGLU activation of their r gate neurons, and the best kappa[k_t][j] of them are executed
+ * (score descending, equal scores to the smaller index); every selected sub-expert inherits
+ * w_j, so routed_scale is the original model's (no factor S).  topk_ids / topk_w are filled
+ * like moe_prism_route's (flat ids e*S + n, appended in rank order, -1 / 0 padded), so
+ * moe_prism_dispatch, _grouped_ffn and _combine follow unchanged.
+ *
+ *   w_proxy   [N, 2*rows_half, d], activation dtype: per original expert the gate rows of its
+ *             gate neurons (neuron c of sub-expert n at row n*r + c), zero rows up to
+ *             rows_half, then their up rows in the same order.  rows_half % 32 == 0,
+ *             rows_half >= S*r.
+ *   kappa     [(m*S + 1), m] int32, device: row k is the split (kappa_1..kappa_m) of budget k,
+ *             0 <= kappa_j <= S, sum k.  Entries outside [0, S] are clamped.
+ *   k_tok     [T] budgets in sub-expert units, 0 <= k_t <= min(k_max, m*S); others are clamped
+ *             and flagged in the status word.
+ * Requirements beyond moe_prism_shape's: m <= N, S <= 16, m*rows_half <= k_max*inter_sub
+ * (MOE_PRISM_ERR_UNSUPPORTED_SHAPE otherwise).  Scores are taken from activations in the
+ * activation dtype (bf16: rounded once) and summed in fp32.  Uses the logits, tile and
+ * intermediate-activation regions of ws and the start of its y region as scratch: do not call
+ * it between moe_prism_grouped_ffn and moe_prism_combine of the same workspace.
+ */
+MOE_PRISM_API int moe_prism_route_proxy(const moe_prism_shape* shape, const void* x,
+                                        const void* w_router0, const float* router_bias0,
+                                        const void* w_proxy, int32_t m, int32_t r,
+                                        int32_t rows_half, const int32_t* kappa,
+                                        const int32_t* k_tok, int32_t* topk_ids, float* topk_w,
+                                        void* ws, size_t ws_bytes, void* stream);
+
+/* moe_prism_layer with the proxy-gate route stage above in place of moe_prism_route. */
+MOE_PRISM_API int moe_prism_layer_proxy(const moe_prism_shape* shape, const void* x,
+                                        const void* w_router0, const float* router_bias0,
+                                        const void* w_proxy, int32_t m, int32_t r,
+                                        int32_t rows_half, const int32_t* kappa,
+                                        const int32_t* k_tok, const void* w_gate_up,
+                                        const void* w_down, void* out, void* ws, size_t ws_bytes,
+                                        void* stream);
+
+/*
  * Where moe_prism_layer keeps its intermediates inside ws (host only): byte
  * offsets of topk_ids, topk_w, group_count, group_offset, sorted_pair,
  * slot_of_pair, y, logits, in that order, into offsets[8].
@@ -176,7 +218,8 @@ MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t*
 #define MOE_PRISM_K_FFN_GATE_UP 6
 #define MOE_PRISM_K_FFN_DOWN 7
 #define MOE_PRISM_K_COMBINE 8
-#define MOE_PRISM_N_KERNELS 9
+#define MOE_PRISM_K_PROXY_SELECT 9
+#define MOE_PRISM_N_KERNELS 10
 MOE_PRISM_API int moe_prism_timing_enable(int on);
 MOE_PRISM_API int moe_prism_timing_read(float* ms, int32_t* calls);
 

@@ -16,10 +16,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmoe_prism.so")
 
 KERNEL_NAMES = ("logits", "topk", "dispatch_count", "dispatch_scan", "dispatch_place",
-                "ffn_tiles", "ffn_gate_up", "ffn_down", "combine")
+                "ffn_tiles", "ffn_gate_up", "ffn_down", "combine", "proxy_select")
 
 EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
+           "moe_prism_route_proxy", "moe_prism_layer_proxy",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
            "moe_prism_timing_read", "moe_prism_strerror")
 
@@ -184,6 +185,56 @@ def moe_prism_status(ws):
     flags, pairs = C.c_int32(0), C.c_int32(0)
     _check(lib().moe_prism_status(_ptr(ws), C.byref(flags), C.byref(pairs), _stream()))
     return flags.value, pairs.value
+
+
+def proxy_to_device(pg, dtype, device="cuda"):
+    """Upload a workloads.ProxyGate: the original router, the gate-neuron rows padded to a
+    multiple of 32 rows per half, and the allocation table."""
+    import numpy as np
+    from . import workloads as W
+
+    def act(a):
+        if dtype == "bf16":
+            bits = W.bf16_bits(a).view(np.int16)
+            return torch.from_numpy(bits).to(device).view(torch.bfloat16).reshape(a.shape)
+        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(device)
+
+    N, two_sr, d = pg.w_proxy.shape
+    sr = two_sr // 2
+    rows_half = (sr + 31) // 32 * 32
+    padded = np.zeros((N, 2 * rows_half, d), np.float32)
+    padded[:, :sr] = pg.w_proxy[:, :sr]
+    padded[:, rows_half:rows_half + sr] = pg.w_proxy[:, sr:]
+    return dict(w_router0=act(pg.w_router0),
+                bias0=None if pg.bias0 is None else torch.from_numpy(pg.bias0).to(device),
+                w_proxy=act(padded), rows_half=rows_half, m=pg.m, r=pg.r,
+                kappa=torch.from_numpy(np.ascontiguousarray(pg.kappa, np.int32)).to(device))
+
+
+def moe_prism_route_proxy(shape, x, pdev, k_tok, ws):
+    """Proxy-gate route stage; pdev from proxy_to_device().  Returns (topk_ids, topk_w)."""
+    T, km = shape.T, shape.k_max
+    ids = torch.empty((T, km), dtype=torch.int32, device=x.device)
+    w = torch.empty((T, km), dtype=torch.float32, device=x.device)
+    _check(lib().moe_prism_route_proxy(C.byref(shape), _ptr(x), _ptr(pdev["w_router0"]),
+                                       _ptr(pdev["bias0"]), _ptr(pdev["w_proxy"]),
+                                       C.c_int32(pdev["m"]), C.c_int32(pdev["r"]),
+                                       C.c_int32(pdev["rows_half"]), _ptr(pdev["kappa"]),
+                                       _ptr(k_tok), _ptr(ids), _ptr(w), _ptr(ws),
+                                       C.c_size_t(ws.numel()), _stream()))
+    return ids, w
+
+
+def moe_prism_layer_proxy(shape, x, pdev, k_tok, w_gate_up, w_down, ws, out=None):
+    if out is None:
+        out = torch.empty((shape.T, shape.d), dtype=act_dtype(shape), device=x.device)
+    _check(lib().moe_prism_layer_proxy(C.byref(shape), _ptr(x), _ptr(pdev["w_router0"]),
+                                       _ptr(pdev["bias0"]), _ptr(pdev["w_proxy"]),
+                                       C.c_int32(pdev["m"]), C.c_int32(pdev["r"]),
+                                       C.c_int32(pdev["rows_half"]), _ptr(pdev["kappa"]),
+                                       _ptr(k_tok), _ptr(w_gate_up), _ptr(w_down), _ptr(out),
+                                       _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return out
 
 
 def moe_prism_timing_enable(on: bool):

@@ -169,6 +169,68 @@ static int do_ffn(const moe_prism_shape* s, const Layout& L, const void* x, cons
   return MOE_PRISM_OK;
 }
 
+// Proxy-gate route stage (Sec. 3.2.2, training-free proxy gating): the original router's
+// top-m experts, a grouped gate-up pass over the gate neurons' rows, per-expert top-kappa.
+// Scratch: the logits, chunk-count, tile and h regions, and the start of the y region.
+struct ProxyScratch {
+  int32_t *ids0, *cnt0, *off0, *sp0, *sl0;
+  float* w0;
+};
+static ProxyScratch proxy_scratch(const moe_prism_shape* s, const Layout& L, char* ws, int m) {
+  char* p = ws + L.y;
+  const size_t n = align256((size_t)s->T * m * 4);
+  ProxyScratch q;
+  q.ids0 = reinterpret_cast<int32_t*>(p);
+  q.w0 = reinterpret_cast<float*>(p + n);
+  q.sp0 = reinterpret_cast<int32_t*>(p + 2 * n);
+  q.sl0 = reinterpret_cast<int32_t*>(p + 3 * n);
+  q.cnt0 = reinterpret_cast<int32_t*>(p + 4 * n);
+  q.off0 = reinterpret_cast<int32_t*>(p + 4 * n + align256((size_t)s->n_experts * 4));
+  return q;
+}
+static int check_proxy(const moe_prism_shape* s, int m, int r, int rows_half) {
+  const long el = s->dtype == MOE_PRISM_F32 ? 4 : 2;
+  if (m <= 0 || r <= 0 || rows_half <= 0) return MOE_PRISM_ERR_INVALID_ARG;
+  if (m > s->n_experts || s->n_sub > PROXY_MAX_SUB || rows_half % 32 != 0 ||
+      rows_half < s->n_sub * r)
+    return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  // the stage's activations [T*m, rows_half] live in the h region, its tables in the y region
+  if ((long)m * rows_half > (long)s->k_max * s->inter_sub) return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  if (4L * align256((size_t)s->T * m * 4) + 2L * align256(((size_t)s->n_experts + 1) * 4) >
+      (long)s->T * s->k_max * s->d * el)
+    return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  return MOE_PRISM_OK;
+}
+static int do_route_proxy(const moe_prism_shape* s, const Layout& L, const void* x,
+                          const void* w_router0, const float* bias0, const void* w_proxy, int m,
+                          int r, int rows_half, const int32_t* kappa, const int32_t* k_tok,
+                          int32_t* ids, float* w, char* ws, hipStream_t st) {
+  const int N = s->n_experts;
+  int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
+  float* logits0 = reinterpret_cast<float*>(ws + L.logits);
+  int32_t* chunk = reinterpret_cast<int32_t*>(ws + L.chunk_cnt);
+  MTile* tiles = reinterpret_cast<MTile*>(ws + L.tiles);
+  void* act = ws + L.h;
+  const ProxyScratch q = proxy_scratch(s, L, ws, m);
+  MP_LAUNCH(MOE_PRISM_K_LOGITS,
+            launch_logits(s->dtype, x, w_router0, bias0, logits0, hdr, s->T, s->d, N, st));
+  MP_LAUNCH(MOE_PRISM_K_TOPK, launch_topk(logits0, nullptr, q.ids0, q.w0, hdr, s->T, N, m,
+                                          s->renormalize, s->routed_scale, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_COUNT, launch_dispatch_count(q.ids0, chunk, s->T, N, m, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, q.cnt0, q.off0, hdr, s->T, N, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_PLACE,
+            launch_dispatch_place(q.ids0, chunk, q.off0, q.sp0, q.sl0, s->T, N, m, st));
+  MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(q.off0, tiles, hdr, N, L.max_mtiles, s->T * m, st));
+  if (s->T == 0) return MOE_PRISM_OK;
+  MP_LAUNCH(MOE_PRISM_K_FFN_GATE_UP,
+            launch_ffn_gate_up(s->dtype, x, w_proxy, q.sp0, tiles, hdr, act, s->T, s->d, rows_half, m,
+                               L.max_mtiles, st));
+  MP_LAUNCH(MOE_PRISM_K_PROXY_SELECT,
+            launch_proxy_select(s->dtype, act, rows_half, q.ids0, q.w0, q.sl0, k_tok, kappa, ids, w,
+                                hdr, s->T, s->n_sub, r, m, s->k_max, st));
+  return MOE_PRISM_OK;
+}
+
 }  // namespace mp
 
 using namespace mp;
@@ -288,6 +350,57 @@ int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_r
   void* y = w8 + L.y;
   int rc = do_route(shape, L, x, w_router, router_bias, k_tok, ids, w,
                     reinterpret_cast<float*>(w8 + L.logits), w8, st);
+  if (rc) return rc;
+  rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st);
+  if (rc) return rc;
+  rc = do_ffn(shape, L, x, w_gate_up, w_down, off, sp, y, w8, st);
+  if (rc) return rc;
+  if (shape->T == 0) return MOE_PRISM_OK;
+  MP_LAUNCH(MOE_PRISM_K_COMBINE, launch_combine(shape->dtype, y, sl, w, k_tok, out, shape->T,
+                                                shape->d, shape->k_max, st));
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_route_proxy(const moe_prism_shape* shape, const void* x, const void* w_router0,
+                          const float* router_bias0, const void* w_proxy, int32_t m, int32_t r,
+                          int32_t rows_half, const int32_t* kappa, const int32_t* k_tok,
+                          int32_t* topk_ids, float* topk_w, void* ws, size_t ws_bytes, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  int rc = check_proxy(shape, m, r, rows_half);
+  if (rc) return rc;
+  if (w_router0 == nullptr || w_proxy == nullptr || kappa == nullptr) return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || topk_ids == nullptr || topk_w == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  return do_route_proxy(shape, L, x, w_router0, router_bias0, w_proxy, m, r, rows_half, kappa, k_tok,
+                        topk_ids, topk_w, static_cast<char*>(ws), (hipStream_t)stream);
+}
+
+int moe_prism_layer_proxy(const moe_prism_shape* shape, const void* x, const void* w_router0,
+                          const float* router_bias0, const void* w_proxy, int32_t m, int32_t r,
+                          int32_t rows_half, const int32_t* kappa, const int32_t* k_tok,
+                          const void* w_gate_up, const void* w_down, void* out, void* ws,
+                          size_t ws_bytes, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  int rc = check_proxy(shape, m, r, rows_half);
+  if (rc) return rc;
+  if (w_router0 == nullptr || w_proxy == nullptr || kappa == nullptr || w_gate_up == nullptr ||
+      w_down == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || out == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  char* w8 = static_cast<char*>(ws);
+  hipStream_t st = (hipStream_t)stream;
+  int32_t* ids = reinterpret_cast<int32_t*>(w8 + L.ids);
+  float* w = reinterpret_cast<float*>(w8 + L.w);
+  int32_t* cnt = reinterpret_cast<int32_t*>(w8 + L.cnt);
+  int32_t* off = reinterpret_cast<int32_t*>(w8 + L.off);
+  int32_t* sp = reinterpret_cast<int32_t*>(w8 + L.sorted_pair);
+  int32_t* sl = reinterpret_cast<int32_t*>(w8 + L.slot_of_pair);
+  void* y = w8 + L.y;
+  rc = do_route_proxy(shape, L, x, w_router0, router_bias0, w_proxy, m, r, rows_half, kappa, k_tok,
+                      ids, w, w8, st);
   if (rc) return rc;
   rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st);
   if (rc) return rc;

@@ -34,6 +34,12 @@ hipError_t launch_topk(const float* logits, const int32_t* k_tok, int32_t* ids, 
 int dispatch_chunk_words(int E, int T);          // 64-token words per chunk
 hipError_t launch_dispatch_count(const int32_t* ids, int32_t* chunk_cnt, int T, int E, int k_max,
                                  hipStream_t s);
+// proxy gate (Sec. 3.2.2): per-expert top-kappa on the gate-neuron activations
+constexpr int PROXY_MAX_SUB = 16;
+hipError_t launch_proxy_select(int dtype, const void* act, int act_ld, const int32_t* ids0,
+                               const float* w0, const int32_t* slot0, const int32_t* k_tok,
+                               const int32_t* kappa, int32_t* ids, float* w, int32_t* hdr, int T,
+                               int S, int r, int m, int k_max, hipStream_t s);
 hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int32_t* off, int32_t* hdr, int T,
                                 int E, hipStream_t s);
 hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* off,

@@ -1,0 +1,135 @@
+"""GPU parity of the proxy-gate route mode (Sec. 3.2.2, training-free proxy gating) through
+the C ABI.  The original router's expert choice is compared bit for bit.  The per-expert
+sub-expert choice is decided by floating-point scores that the device takes from activations
+in the activation dtype, so it is compared with a margin: the device's choice must be the
+oracle's wherever the oracle's scores are separated by more than the tolerance, and must lie
+inside the tie set elsewhere."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2510_19366_amd import binding as B
+from paper_2510_19366_amd import workloads as W
+from gpu_util import max_rel, run_layer, to_np
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = {"f32": 2e-5, "bf16": 2e-2}      # relative to the largest score of the expert
+OUT_TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def make(dtype, T, d, N, I, S, m, r, seed, bias_std=0.0):
+    whole = W.make_workload("whole", dtype=dtype, d=d, n_experts=N, n_sub=1, inter_sub=I,
+                            req_tokens=[T], req_k=[m], k_max=m, seed=seed, routed_scale=1.0,
+                            w_std=0.05, bias_std=bias_std)
+    split = W.split_workload(whole, S)
+    split.k_max = m * S
+    split.routed_scale = 1.0                      # sub-experts inherit the expert's weight
+    pg = W.make_proxy_gate(whole, split, m=m, r=r, seed=seed + 1)
+    return whole, split, pg
+
+
+def check_route(split, pg, k_tok, ids, w, dtype):
+    """ids/w from the device against the oracle's scores.  Returns the mask of tokens whose
+    ids equal the oracle's exactly."""
+    S, m = split.n_sub, pg.m
+    ref = O.route_proxy(split.x, pg.w_router0, pg.bias0, pg.w_proxy, k_tok, pg.kappa, S, pg.r, m,
+                        split.k_max, split.renormalize, 1.0, return_all=True)
+    tol = SCORE_TOL[dtype]
+    same = np.ones(split.T, bool)
+    for t in range(split.T):
+        kt = int(np.clip(k_tok[t], 0, m * S))
+        got = ids[t]
+        assert np.all(got[kt:] == -1) and np.all(w[t, kt:] == 0) and np.all(got[:kt] >= 0)
+        pos = 0
+        for j in range(m):
+            kap = int(pg.kappa[kt, j])
+            mine = got[pos:pos + kap]
+            e = ref["ids0"][t, j]
+            assert np.all(mine // S == e), (t, j)                       # expert choice: exact
+            np.testing.assert_allclose(w[t, pos:pos + kap], ref["w0"][t, j], rtol=2e-5)
+            sub = mine % S
+            assert len(set(sub.tolist())) == kap
+            s = ref["scores"][t, j]
+            eps = tol * s.max()
+            if kap:
+                kth = np.sort(s)[::-1][kap - 1]
+                assert np.all(s[sub] >= kth - eps), (t, j, s, sub)       # nothing clearly worse picked
+                rest = np.setdiff1d(np.arange(S), sub)
+                assert np.all(s[rest] <= kth + eps), (t, j, s, sub)      # nothing clearly better left out
+                assert np.all(np.diff(s[sub]) <= eps)                    # best first
+            pos += kap
+        assert pos == kt
+        same[t] = np.array_equal(got, ref["ids"][t])
+    return same, ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [
+    dict(T=300, d=128, N=8, I=128, S=4, m=3, r=4),
+    dict(T=1100, d=256, N=24, I=192, S=2, m=6, r=16),
+    dict(T=64, d=64, N=4, I=256, S=8, m=2, r=3),
+])
+def test_proxy_route_and_layer_against_oracle(dtype, case):
+    whole, split, pg = make(dtype, seed=case["T"], bias_std=0.5, **case)
+    rng = np.random.default_rng(case["T"])
+    k_tok = rng.integers(0, pg.m * split.n_sub + 1, size=split.T).astype(np.int32)
+    dev = B.to_device(split)
+    pdev = B.proxy_to_device(pg, dtype)
+    shape = dev["shape"]
+    ws = B.alloc_workspace(shape)
+    k_dev = torch.from_numpy(k_tok).cuda()
+    ids, w = B.moe_prism_route_proxy(shape, dev["x"], pdev, k_dev, ws)
+    torch.cuda.synchronize()
+    flags, _ = B.moe_prism_status(ws)
+    assert flags == 0
+    same, ref = check_route(split, pg, k_tok, to_np(ids), to_np(w), dtype)
+    assert same.mean() >= (1.0 if dtype == "f32" else 0.9), same.mean()
+    # the fused layer: same routing, then the usual dispatch / FFN / combine
+    out = B.moe_prism_layer_proxy(shape, dev["x"], pdev, k_dev, dev["w_gate_up"], dev["w_down"], ws)
+    torch.cuda.synchronize()
+    inter = {k: to_np(v) for k, v in B.layer_intermediates(shape, ws).items()}
+    assert np.array_equal(inter["topk_ids"], to_np(ids))
+    cnt, off, sp, sl = O.dispatch(ref["ids"], split.E)
+    y = O.grouped_ffn(split.x, split.w_gate_up, split.w_down, off, sp, split.k_max)
+    ref_out = O.combine(y, sl, ref["w"], np.clip(k_tok, 0, split.k_max).astype(np.int32), split.T)
+    got = to_np(out)
+    assert max_rel(got[same], ref_out[same]) <= OUT_TOL[dtype]
+    assert np.all(got[k_tok == 0] == 0)
+    if same.all():                                   # identical routing: tables are comparable too
+        assert np.array_equal(inter["group_offset"], off) and np.array_equal(inter["sorted_pair"], sp)
+
+
+def test_full_allocation_reconstructs_the_undivided_layer():
+    # every selected expert gets all S of its sub-experts: the refactored layer is the original one
+    whole, split, pg = make("bf16", T=2048, d=256, N=16, I=256, S=4, m=4, r=8, seed=7)
+    dev_w = B.to_device(whole)
+    out_w, _, _ = run_layer(whole, dev_w)
+    dev = B.to_device(split)
+    pdev = B.proxy_to_device(pg, "bf16")
+    ws = B.alloc_workspace(dev["shape"])
+    k_dev = torch.full((split.T,), pg.m * split.n_sub, dtype=torch.int32, device="cuda")
+    out = B.moe_prism_layer_proxy(dev["shape"], dev["x"], pdev, k_dev, dev["w_gate_up"],
+                                  dev["w_down"], ws)
+    torch.cuda.synchronize()
+    _, pairs = B.moe_prism_status(ws)
+    assert pairs == split.T * pg.m * split.n_sub
+    assert max_rel(to_np(out), to_np(out_w)) <= 2e-2
+
+
+def test_proxy_argument_errors_and_clamping():
+    whole, split, pg = make("bf16", T=50, d=64, N=4, I=128, S=4, m=2, r=4, seed=3)
+    dev = B.to_device(split)
+    pdev = B.proxy_to_device(pg, "bf16")
+    shape = dev["shape"]
+    ws = B.alloc_workspace(shape)
+    k_bad = torch.full((split.T,), 99, dtype=torch.int32, device="cuda")
+    ids, w = B.moe_prism_route_proxy(shape, dev["x"], pdev, k_bad, ws)
+    flags, _ = B.moe_prism_status(ws)
+    assert flags & 1 and np.all(to_np(ids) >= 0)          # clamped to m*S and flagged
+    for key, val in (("m", 0), ("m", 5), ("rows_half", 48), ("rows_half", 0), ("r", 0)):
+        bad = dict(pdev)
+        bad[key] = val
+        with pytest.raises(B.MoePrismError):
+            B.moe_prism_route_proxy(shape, dev["x"], bad, k_bad, ws)
