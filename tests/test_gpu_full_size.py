@@ -76,3 +76,38 @@ def test_c5_matched_budget_split_vs_whole(T):
     got_a, _ = check_full(a, n_sample=32, seed=1)
     got_b, _ = check_full(b, n_sample=32, seed=1)
     assert max_rel(got_b, got_a) <= 2e-2
+
+
+def test_proxy_gate_full_size_sampled():
+    # Sec. 3.2.2 training-free proxy gate at the benchmark's size (bench.py --route proxy):
+    # 128 experts split in 4, m = 8, r = 4, per-request budgets in [8, 32]; routing checked with
+    # the margin rule and outputs against the oracle on a random sample of tokens
+    from paper_2510_19366_amd.compare_modes import request_budgets
+    from test_gpu_proxy import OUT_TOL, check_route
+    whole = W.config("c5a_s1_k8", T=16384)
+    split = W.split_workload(whole, 4)
+    split.routed_scale = 1.0
+    _, k_tok = request_budgets(split.T, 64, 8, 32, seed=3)
+    pg = W.make_proxy_gate(whole, split, m=8, r=4, seed=6)
+    dev = B.to_device(split)
+    pdev = B.proxy_to_device(pg, "bf16")
+    shape = dev["shape"]
+    ws = B.alloc_workspace(shape)
+    k_dev = torch.from_numpy(k_tok).cuda()
+    out = B.moe_prism_layer_proxy(shape, dev["x"], pdev, k_dev, dev["w_gate_up"], dev["w_down"], ws)
+    torch.cuda.synchronize()
+    flags, pairs = B.moe_prism_status(ws)
+    assert flags == 0 and pairs == int(k_tok.sum())
+    inter = {k: to_np(v) for k, v in B.layer_intermediates(shape, ws).items()}
+    ids, w = inter["topk_ids"], inter["topk_w"]
+    assert np.array_equal((ids >= 0).sum(1), k_tok)
+    tok = np.sort(np.random.default_rng(2).choice(split.T, size=48, replace=False))
+    sub = W.Workload(**{**split.__dict__, "T": len(tok), "x": split.x[tok], "k_tok": k_tok[tok]})
+    same, ref = check_route(sub, pg, k_tok[tok], ids[tok], w[tok], "bf16")
+    assert same.mean() >= 0.9
+    got = to_np(out)[tok]
+    for i in np.nonzero(same)[0]:
+        want = sum(ref["w"][i, j] * O.ffn_one(sub.x[i], split.w_gate_up[ref["ids"][i, j]],
+                                              split.w_down[ref["ids"][i, j]])
+                   for j in range(k_tok[tok[i]]))
+        assert max_rel(got[i], want) <= OUT_TOL["bf16"]
