@@ -114,6 +114,36 @@ def test_wide_router_and_large_k():
     check_against_oracle(wl, r, ref)
 
 
+def test_largest_supported_router_and_budget():
+    # the documented limits: E = 4096 sub-experts (64 logits per lane), k_max = 1024
+    T = 40
+    k = np.random.default_rng(5).integers(0, 1025, size=T).astype(np.int32)
+    k[:3] = [1024, 0, 1]
+    wl = W.make_workload("max", dtype="bf16", d=64, n_experts=1024, n_sub=4, inter_sub=32,
+                         req_tokens=[1] * T, req_k=k, k_max=1024, seed=5, w_std=0.1)
+    r = run_stages(wl)
+    ref = O.layer_of(wl, return_all=True)
+    check_against_oracle(wl, r, ref)
+    # one past either limit is refused on the host
+    for bad in (B.make_shape(T, 64, 1025, 4, 32, 8, "bf16"), B.make_shape(T, 64, 1024, 4, 32, 1025, "bf16")):
+        with pytest.raises(B.MoePrismError) as e:
+            B.alloc_workspace(bad)
+        assert e.value.code == -2
+
+
+def test_everything_routed_to_one_sub_expert():
+    # the degenerate load: one group holds all T rows (many m-tiles), every other group is empty
+    T = 3000
+    wl = W.make_workload("one", dtype="bf16", d=128, n_experts=8, n_sub=4, inter_sub=64,
+                         req_tokens=[T], req_k=[1], k_max=2, seed=9, w_std=0.05)
+    wl.router_bias = np.zeros(wl.E, np.float32)
+    wl.router_bias[13] = 1000.0
+    r = run_stages(wl)
+    assert r["cnt"][13] == T and r["cnt"].sum() == T
+    ref = O.layer_of(wl, return_all=True)
+    check_against_oracle(wl, r, ref)
+
+
 @pytest.mark.parametrize("scale", [1.0, 1e-19])
 @pytest.mark.parametrize("T,E", [(6200, 1000), (2100, 500), (300, 100)])
 def test_matrix_core_logits_are_the_same_chain(T, E, scale):
