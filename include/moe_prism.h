@@ -198,6 +198,42 @@ MOE_PRISM_API int moe_prism_layer_proxy(const moe_prism_shape* shape, const void
  */
 MOE_PRISM_API int moe_prism_layer_offsets(const moe_prism_shape* shape, size_t* offsets);
 
+/*
+ * Offline quality-tiered batching (Sec. 3.3.2, temporal separation; Eq. 5).  HOST ONLY: all
+ * pointers are host pointers, nothing touches the GPU.
+ *
+ * The R waiting requests (arrival time, prompt tokens n_i > 0, budget k_i >= 0 in sub-expert
+ * units) are sorted by (k, arrival, index) and cut into batches of at most M tokens, filled
+ * strictly in that order.  A tier's under-filled last batch (n_cur tokens at budget k) is
+ * promoted to the next tier's budget k_next and merged with it when
+ *     (n_cur + n_next) * T(n_cur, k) >= n_cur * T(n_cur + n_next, k_next)      (binary64)
+ * where n_next is the longest prefix of the next tier that fits in M - n_cur (none: no merge),
+ * else it is dispatched at k.  A request longer than M forms a batch of its own.
+ *
+ *   table        T(n, k) in milliseconds on a grid: n_grid[n_n], k_grid[n_k] strictly
+ *                ascending, ms[n_n * n_k] row-major in n; bilinear between grid points,
+ *                constant outside (e.g. as printed by compare_modes --table).
+ *   order        [R] out: request indices in dispatch order.
+ *   batch_start  [R + 1] out: batch b is order[batch_start[b] .. batch_start[b+1]).
+ *   batch_k      [R] out: the budget batch b runs at when the whole batch runs at one budget
+ *                (its largest member budget).  With per-token budgets (moe_prism_layer) every
+ *                request keeps its own k and batch_k is only the planner's accounting.
+ *   n_batches    out.
+ * Returns MOE_PRISM_OK or MOE_PRISM_ERR_INVALID_ARG.
+ */
+typedef struct {
+  int32_t n_n, n_k;
+  const int32_t* n_grid;
+  const int32_t* k_grid;
+  const float* ms;
+} moe_prism_time_table;
+
+MOE_PRISM_API int moe_prism_plan_batches(int32_t R, const double* arrival, const int32_t* n_tokens,
+                                         const int32_t* k_qos, int32_t M,
+                                         const moe_prism_time_table* table, int32_t* order,
+                                         int32_t* batch_start, int32_t* batch_k,
+                                         int32_t* n_batches);
+
 /* Debug: synchronises `stream`, copies the status word to *host_flags and the
  * number of pairs of the last dispatch to *host_pairs (either may be NULL). */
 MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t* host_pairs, void* stream);

@@ -20,7 +20,7 @@ KERNEL_NAMES = ("logits", "topk", "dispatch_count", "dispatch_scan", "dispatch_p
 
 EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
-           "moe_prism_route_proxy", "moe_prism_layer_proxy",
+           "moe_prism_route_proxy", "moe_prism_layer_proxy", "moe_prism_plan_batches",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
            "moe_prism_timing_read", "moe_prism_strerror")
 
@@ -235,6 +235,40 @@ def moe_prism_layer_proxy(shape, x, pdev, k_tok, w_gate_up, w_down, ws, out=None
                                        _ptr(k_tok), _ptr(w_gate_up), _ptr(w_down), _ptr(out),
                                        _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return out
+
+
+class TimeTable(C.Structure):
+    _fields_ = [("n_n", C.c_int32), ("n_k", C.c_int32), ("n_grid", C.POINTER(C.c_int32)),
+                ("k_grid", C.POINTER(C.c_int32)), ("ms", C.POINTER(C.c_float))]
+
+
+def moe_prism_plan_batches(arrival, n_tokens, k_qos, M, n_grid, k_grid, ms):
+    """Offline quality-tiered batching (host only, numpy in and out).
+    Returns (batches, batch_k): lists of request indices per batch in dispatch order."""
+    import numpy as np
+    arrival = np.ascontiguousarray(arrival, np.float64)
+    n_tokens = np.ascontiguousarray(n_tokens, np.int32)
+    k_qos = np.ascontiguousarray(k_qos, np.int32)
+    n_grid = np.ascontiguousarray(n_grid, np.int32)
+    k_grid = np.ascontiguousarray(k_grid, np.int32)
+    ms = np.ascontiguousarray(ms, np.float32)
+    assert ms.shape == (n_grid.size, k_grid.size)
+    R = int(k_qos.size)
+    tab = TimeTable(n_grid.size, k_grid.size, n_grid.ctypes.data_as(C.POINTER(C.c_int32)),
+                    k_grid.ctypes.data_as(C.POINTER(C.c_int32)),
+                    ms.ctypes.data_as(C.POINTER(C.c_float)))
+    order = np.empty(max(R, 1), np.int32)
+    start = np.empty(R + 1, np.int32)
+    bk = np.empty(max(R, 1), np.int32)
+    nb = C.c_int32(0)
+    _check(lib().moe_prism_plan_batches(
+        C.c_int32(R), arrival.ctypes.data_as(C.POINTER(C.c_double)),
+        n_tokens.ctypes.data_as(C.POINTER(C.c_int32)), k_qos.ctypes.data_as(C.POINTER(C.c_int32)),
+        C.c_int32(int(M)), C.byref(tab), order.ctypes.data_as(C.POINTER(C.c_int32)),
+        start.ctypes.data_as(C.POINTER(C.c_int32)), bk.ctypes.data_as(C.POINTER(C.c_int32)),
+        C.byref(nb)))
+    n = nb.value
+    return [order[start[b]:start[b + 1]].tolist() for b in range(n)], bk[:n].tolist()
 
 
 def moe_prism_timing_enable(on: bool):
