@@ -114,6 +114,29 @@ def test_wide_router_and_large_k():
     check_against_oracle(wl, r, ref)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_full_oracle(seed):
+    # seeded random layer shapes: K lengths on both sides of every kernel-selection threshold
+    # (register-staged, in-step ring, two-group ring; 192- and 256-wide tiles; all three logits
+    # kernels' neighbours), ragged groups, empty groups, budgets from 0 to k_max
+    rng = np.random.default_rng(1000 + seed)
+    d = 64 * int(rng.integers(1, 11))
+    Is = 32 * int(rng.integers(1, 14))
+    N, S = int(rng.integers(1, 7)), int(rng.choice([1, 2, 4]))
+    T = int(rng.choice([1, 37, 256, 700, 1300, 2500]))
+    k_max = int(rng.integers(1, min(N * S, 12) + 1))
+    k = rng.integers(0, k_max + 1, size=T).astype(np.int32)
+    dtype = "bf16" if seed % 4 else "f32"
+    wl = W.make_workload("rnd", dtype=dtype, d=d, n_experts=N, n_sub=S, inter_sub=Is,
+                         req_tokens=[1] * T, req_k=k, k_max=k_max, seed=seed, bias_std=1.0,
+                         w_std=0.05, renormalize=int(rng.integers(0, 2)))
+    r = run_stages(wl)
+    ref = O.layer_of(wl, return_all=True)
+    check_against_oracle(wl, r, ref)
+    out, _, _ = run_layer(wl, r["dev"], r["ws"])
+    assert np.array_equal(to_np(out), r["out"])
+
+
 def test_largest_supported_router_and_budget():
     # the documented limits: E = 4096 sub-experts (64 logits per lane), k_max = 1024
     T = 40
