@@ -21,7 +21,9 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (see profiles/); None until measured for that workload.
-TRAFFIC_BYTES = {"c3_fine_128x4": 2.27e9}   # gate-up kernel: 2.143 GB fetched + 0.122 GB written
+TRAFFIC_BYTES = {"c3_fine_128x4": 2.27e9,   # gate-up kernel: 2.143 GB fetched + 0.122 GB written
+                 "c2_mixtral_8x4": 4.51e9,  # 4.361 + 0.152 (weights of a group reach several XCDs' L2)
+                 "c4_decode_64x2": 1.70e9}  # 1.608 + 0.093
 
 
 def main():
