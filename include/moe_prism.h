@@ -244,6 +244,9 @@ MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t*
  * moe_prism_timing_read synchronises on the recorded events, adds the elapsed
  * milliseconds of each kernel since the last reset into ms[MOE_PRISM_N_KERNELS]
  * (host), the launch counts into calls[...] (host), and resets.
+ * moe_prism_timing_select restricts the bracketing to the kernels whose bit
+ * (1 << MOE_PRISM_K_*) is set in kernel_mask (default: all), e.g. to time one
+ * kernel inside a throughput measurement without event records around the rest.
  */
 #define MOE_PRISM_K_LOGITS 0
 #define MOE_PRISM_K_TOPK 1
@@ -257,6 +260,7 @@ MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t*
 #define MOE_PRISM_K_PROXY_SELECT 9
 #define MOE_PRISM_N_KERNELS 10
 MOE_PRISM_API int moe_prism_timing_enable(int on);
+MOE_PRISM_API int moe_prism_timing_select(uint32_t kernel_mask);
 MOE_PRISM_API int moe_prism_timing_read(float* ms, int32_t* calls);
 
 MOE_PRISM_API const char* moe_prism_strerror(int code);

@@ -22,7 +22,7 @@ EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
            "moe_prism_route_proxy", "moe_prism_layer_proxy", "moe_prism_plan_batches",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
-           "moe_prism_timing_read", "moe_prism_strerror")
+           "moe_prism_timing_select", "moe_prism_timing_read", "moe_prism_strerror")
 
 
 class Shape(C.Structure):
@@ -273,6 +273,12 @@ def moe_prism_plan_batches(arrival, n_tokens, k_qos, M, n_grid, k_grid, ms):
 
 def moe_prism_timing_enable(on: bool):
     _check(lib().moe_prism_timing_enable(1 if on else 0))
+
+
+def moe_prism_timing_select(names=None):
+    """Time only the named kernels (KERNEL_NAMES); None = all."""
+    mask = 0xFFFFFFFF if names is None else sum(1 << KERNEL_NAMES.index(n) for n in names)
+    _check(lib().moe_prism_timing_select(C.c_uint32(mask)))
 
 
 def moe_prism_timing_read():

@@ -81,6 +81,7 @@ struct Rec {
 };
 static std::mutex g_mu;
 static bool g_timing = false;
+static uint32_t g_timing_mask = ~0u;  // bit k: kernel id k is timed
 static std::vector<Rec> g_recs;
 static std::vector<hipEvent_t> g_pool;
 
@@ -101,7 +102,7 @@ struct Timed {  // brackets one kernel launch with events when timing is on
   bool on = false;
   Timed(int kernel, hipStream_t st) : s(st) {
     std::lock_guard<std::mutex> lk(g_mu);
-    if (!g_timing) return;
+    if (!g_timing || ((g_timing_mask >> kernel) & 1u) == 0) return;
     on = true;
     r.kernel = kernel;
     r.a = get_event();
@@ -427,6 +428,12 @@ int moe_prism_status(const void* ws, int32_t* host_flags, int32_t* host_pairs, v
 int moe_prism_timing_enable(int on) {
   std::lock_guard<std::mutex> lk(g_mu);
   g_timing = on != 0;
+  return MOE_PRISM_OK;
+}
+
+int moe_prism_timing_select(uint32_t kernel_mask) {
+  std::lock_guard<std::mutex> lk(g_mu);
+  g_timing_mask = kernel_mask;
   return MOE_PRISM_OK;
 }
 
