@@ -57,3 +57,31 @@ def test_one_graph_serves_every_budget_mix():
         assert flags == 0 and pairs == int(k.sum()), (i, flags, pairs)
         assert torch.equal(out_g.view(torch.int16), out_e.view(torch.int16)), i
         assert np.all(to_np(out_g)[k == 0] == 0)
+
+
+def test_timing_select_brackets_only_the_named_kernels():
+    wl = W.config("c4_decode_64x2", scale_down=32)
+    dev = B.to_device(wl)
+    ws = B.alloc_workspace(dev["shape"])
+
+    def layer():
+        B.moe_prism_layer(dev["shape"], dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"],
+                          dev["w_gate_up"], dev["w_down"], ws)
+    layer()
+    torch.cuda.synchronize()
+    try:
+        B.moe_prism_timing_select(["ffn_gate_up", "combine"])
+        B.moe_prism_timing_enable(True)
+        B.moe_prism_timing_read()
+        for _ in range(3):
+            layer()
+        t = B.moe_prism_timing_read()
+        assert {k for k, v in t.items() if v[1]} == {"ffn_gate_up", "combine"}
+        assert t["ffn_gate_up"][1] == 3 and t["ffn_gate_up"][0] > 0
+        B.moe_prism_timing_select(None)
+        layer()
+        t = B.moe_prism_timing_read()
+        assert all(v[1] == 1 for k, v in t.items() if k != "proxy_select") and t["proxy_select"][1] == 0
+    finally:
+        B.moe_prism_timing_select(None)
+        B.moe_prism_timing_enable(False)
