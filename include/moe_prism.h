@@ -234,6 +234,34 @@ MOE_PRISM_API int moe_prism_plan_batches(int32_t R, const double* arrival, const
                                          int32_t* batch_start, int32_t* batch_k,
                                          int32_t* n_batches);
 
+/*
+ * Partition solver (Sec. 3.2.1, "Partition Optimization Solver"; objective Eq. 4).  HOST ONLY,
+ * offline.  A [B, C] fp32: calibration activations of one expert (B routed tokens, C intermediate
+ * neurons); group_of [C]: the sub-expert (0..S-1) of every neuron; S <= 64, C % S == 0.
+ * With L[b, n] = sum of |A[b, c]| over the neurons of group n (binary64, ascending c) the
+ * objective for an inner budget k_in is  sum_b (sum of the S - k_in smallest L[b, .]).
+ *   _greedy     neurons by descending calibration-wide L1 norm (equal norms: ascending index),
+ *               each to the group with the smallest accumulated norm that still has room
+ *               (equal sums: lower group).  Writes group_of.
+ *   _objective  the loss of a given equal-sized partition.
+ *   _anneal     `steps` proposals; proposal s swaps neurons r0 % C and r1 % C where
+ *               r_i = splitmix64(seed + 3 s + i) (skipped if both are in one group); a swap that
+ *               does not raise the loss is kept, one that raises it by D with probability
+ *               exp(-D / temp), u = (r2 >> 11) * 2^-53, temp = t0 (t1/t0)^(s/(steps-1)).
+ *               group_of is the starting partition on entry and the result on return;
+ *               *loss_out (may be NULL) is its loss.
+ * Returns MOE_PRISM_OK or MOE_PRISM_ERR_INVALID_ARG (including a group_of that is not an
+ * equal-sized partition).
+ */
+MOE_PRISM_API int moe_prism_partition_greedy(int32_t B, int32_t C, int32_t S, const float* A,
+                                             int32_t* group_of);
+MOE_PRISM_API int moe_prism_partition_objective(int32_t B, int32_t C, int32_t S, int32_t k_in,
+                                                const float* A, const int32_t* group_of,
+                                                double* loss);
+MOE_PRISM_API int moe_prism_partition_anneal(int32_t B, int32_t C, int32_t S, int32_t k_in,
+                                             const float* A, int32_t* group_of, int64_t steps,
+                                             double t0, double t1, uint64_t seed, double* loss_out);
+
 /* Debug: synchronises `stream`, copies the status word to *host_flags and the
  * number of pairs of the last dispatch to *host_pairs (either may be NULL). */
 MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t* host_pairs, void* stream);

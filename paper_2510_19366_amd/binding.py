@@ -21,6 +21,7 @@ KERNEL_NAMES = ("logits", "topk", "dispatch_count", "dispatch_scan", "dispatch_p
 EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
            "moe_prism_route_proxy", "moe_prism_layer_proxy", "moe_prism_plan_batches",
+           "moe_prism_partition_greedy", "moe_prism_partition_objective", "moe_prism_partition_anneal",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
            "moe_prism_timing_select", "moe_prism_timing_read", "moe_prism_strerror")
 
@@ -269,6 +270,47 @@ def moe_prism_plan_batches(arrival, n_tokens, k_qos, M, n_grid, k_grid, ms):
         C.byref(nb)))
     n = nb.value
     return [order[start[b]:start[b + 1]].tolist() for b in range(n)], bk[:n].tolist()
+
+
+def _part_args(A):
+    import numpy as np
+    A = np.ascontiguousarray(A, np.float32)
+    return A, A.ctypes.data_as(C.POINTER(C.c_float))
+
+
+def moe_prism_partition_greedy(A, S):
+    """Greedy initial partition (host only): group_of [C] int32."""
+    import numpy as np
+    A, pA = _part_args(A)
+    g = np.empty(A.shape[1], np.int32)
+    _check(lib().moe_prism_partition_greedy(C.c_int32(A.shape[0]), C.c_int32(A.shape[1]),
+                                            C.c_int32(S), pA, g.ctypes.data_as(C.POINTER(C.c_int32))))
+    return g
+
+
+def moe_prism_partition_objective(A, group_of, S, k_in):
+    import numpy as np
+    A, pA = _part_args(A)
+    g = np.ascontiguousarray(group_of, np.int32)
+    loss = C.c_double(0.0)
+    _check(lib().moe_prism_partition_objective(C.c_int32(A.shape[0]), C.c_int32(A.shape[1]),
+                                               C.c_int32(S), C.c_int32(k_in), pA,
+                                               g.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(loss)))
+    return loss.value
+
+
+def moe_prism_partition_anneal(A, group_of, S, k_in, steps, t0, t1, seed):
+    """Simulated annealing from group_of (host only): (new group_of, loss)."""
+    import numpy as np
+    A, pA = _part_args(A)
+    g = np.array(group_of, np.int32)
+    loss = C.c_double(0.0)
+    _check(lib().moe_prism_partition_anneal(C.c_int32(A.shape[0]), C.c_int32(A.shape[1]),
+                                            C.c_int32(S), C.c_int32(k_in), pA,
+                                            g.ctypes.data_as(C.POINTER(C.c_int32)),
+                                            C.c_int64(int(steps)), C.c_double(t0), C.c_double(t1),
+                                            C.c_uint64(int(seed)), C.byref(loss)))
+    return g, loss.value
 
 
 def moe_prism_timing_enable(on: bool):

@@ -1,0 +1,93 @@
+"""Partition solver (Sec. 3.2.1, Eq. 4): the plain reference pinned to the definition, hand
+cases and brute force, and the library's host implementation compared with it exactly.
+No GPU involved.  Calibration activations are synthetic: neurons that fire together in blocks,
+hidden by a random permutation, plus noise (the paper profiles a pretrained model)."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import partition_oracle as PO
+from paper_2510_19366_amd import binding as B
+
+
+def synthetic_activations(seed, B_tok=48, C=32, S=4, noise=0.05):
+    """Each token excites one hidden block of C/S neurons strongly; the blocks are scattered
+    over the neuron indices by a random permutation."""
+    rng = np.random.default_rng(seed)
+    perm = rng.permutation(C)
+    A = noise * rng.standard_normal((B_tok, C))
+    for b in range(B_tok):
+        blk = rng.integers(0, S)
+        A[b, perm[blk * (C // S):(blk + 1) * (C // S)]] += rng.standard_normal(C // S) + 2.0
+    return A.astype(np.float32), perm
+
+
+def test_objective_is_the_definition():
+    A, _ = synthetic_activations(1)
+    rng = np.random.default_rng(1)
+    g = np.repeat(np.arange(4), 8)[rng.permutation(32)].astype(np.int32)
+    for k_in in range(5):
+        L = np.stack([np.abs(A[:, g == n]).astype(np.float64).sum(1) for n in range(4)], axis=1)
+        want = np.sort(L, axis=1)[:, :4 - k_in].sum()
+        assert PO.objective(A, g, 4, k_in) == pytest.approx(want, rel=1e-12)
+    assert PO.objective(A, g, 4, 4) == 0.0                                # nothing dropped
+
+
+def test_greedy_hand_case():
+    # one token, norms 8..1, two groups of four: 8->g0, 7->g1, 6->g1 (7<8), 5->g0 (8<13),
+    # 4->g0 (13=13: lower group), 3->g1, 2->g1 (16<17), then g1 is full: 1->g0
+    A = np.array([[8, 7, 6, 5, 4, 3, 2, 1]], np.float32)
+    assert PO.greedy(A, 2).tolist() == [0, 1, 1, 0, 0, 1, 1, 0]
+    # equal norms: ascending index, alternating groups
+    assert PO.greedy(np.ones((3, 6), np.float32), 3).tolist() == [0, 1, 2, 0, 1, 2]
+
+
+def test_anneal_reaches_the_brute_force_optimum_on_a_tiny_instance():
+    A, _ = synthetic_activations(3, B_tok=20, C=8, S=2, noise=0.02)
+    best = min(PO.objective(A, np.isin(np.arange(8), c).astype(np.int32), 2, 1)
+               for c in itertools.combinations(range(8), 4))
+    g0 = PO.greedy(A, 2)
+    g, loss = PO.anneal(A, g0, 2, 1, steps=3000, t0=1.0, t1=1e-3, seed=5)
+    assert loss == pytest.approx(best, rel=1e-9)
+    assert loss == pytest.approx(PO.objective(A, g, 2, 1), rel=1e-9)      # incremental = from scratch
+    assert np.bincount(g, minlength=2).tolist() == [4, 4]
+
+
+def test_anneal_recovers_hidden_blocks_and_never_worsens_when_cold():
+    A, perm = synthetic_activations(4)
+    g0 = PO.greedy(A, 4)
+    l0 = PO.objective(A, g0, 4, 1)
+    g, loss = PO.anneal(A, g0, 4, 1, steps=4000, t0=1e-9, t1=1e-9, seed=7)   # cold: pure descent
+    assert loss <= l0 and np.bincount(g, minlength=4).tolist() == [8] * 4
+    g, loss = PO.anneal(A, g0, 4, 1, steps=20000, t0=2.0, t1=1e-3, seed=7)
+    assert loss < 0.5 * l0
+    hidden = np.empty(32, np.int64)
+    hidden[perm] = np.repeat(np.arange(4), 8)
+    # every recovered group is (almost) one hidden block
+    purity = [np.bincount(hidden[g == n], minlength=4).max() for n in range(4)]
+    assert sum(purity) >= 28
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_library_equals_reference(seed):
+    S = [2, 4, 4, 8][seed]
+    A, _ = synthetic_activations(10 + seed, B_tok=40, C=32, S=S)
+    g_ref = PO.greedy(A, S)
+    g_lib = B.moe_prism_partition_greedy(A, S)
+    assert np.array_equal(g_lib, g_ref)
+    for k_in in (1, S // 2):
+        assert B.moe_prism_partition_objective(A, g_ref, S, k_in) == PO.objective(A, g_ref, S, k_in)
+        ref = PO.anneal(A, g_ref, S, k_in, steps=3000, t0=1.0, t1=1e-3, seed=100 + seed)
+        got = B.moe_prism_partition_anneal(A, g_ref, S, k_in, 3000, 1.0, 1e-3, 100 + seed)
+        assert np.array_equal(got[0], ref[0]) and got[1] == ref[1]
+
+
+def test_library_argument_checks():
+    A = np.ones((4, 8), np.float32)
+    with pytest.raises(B.MoePrismError):
+        B.moe_prism_partition_greedy(A, 3)                               # C % S != 0
+    with pytest.raises(B.MoePrismError):
+        B.moe_prism_partition_objective(A, np.zeros(8, np.int32), 2, 1)  # not equal-sized
+    with pytest.raises(B.MoePrismError):
+        B.moe_prism_partition_anneal(A, np.array([0, 1] * 4, np.int32), 2, 1, 10, 0.0, 1.0, 1)
