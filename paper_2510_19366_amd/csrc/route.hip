@@ -423,10 +423,8 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
   for (int j = 0; j < kt; ++j) {
     const float top = wave_max_f(bg == NONE ? NEG_INF : bv);
     const int g = wave_min_i((bg != NONE && bv == top) ? bg : NONE);
-    const float e = expf(top - mx);
-    dsel += e;
     if (lane == 0) {
-      se[j] = e;
+      se[j] = top;  // exponentials are taken for all picks at once after the loop
       sid[j] = g;
     }
     if ((g & 63) == lane) {  // the winner retires its element and rescans its own logits
@@ -443,13 +441,14 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
       }
     }
   }
-  if (renorm) denom = dsel;
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of lane 0 are done
+  for (int j = lane; j < kt; j += 64) dsel += expf(se[j] - mx);
+  if (renorm) denom = wave_sum(dsel);
   for (int j = lane; j < k_max; j += 64) {
     bool on = j < kt;
     ids[(size_t)t * k_max + j] = on ? sid[j] : -1;
-    wout[(size_t)t * k_max + j] = on ? scale * se[j] / denom : 0.0f;
+    wout[(size_t)t * k_max + j] = on ? scale * expf(se[j] - mx) / denom : 0.0f;
   }
 }
 
