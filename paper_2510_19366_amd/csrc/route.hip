@@ -473,12 +473,13 @@ hipError_t launch_topk(const float* logits, const int32_t* k_tok, int32_t* ids, 
 }
 
 // ---------------------------------------------------------------- proxy gate: per-expert top-kappa
-// Sec. 3.2.2, training-free proxy gating.  One thread per token.  For the expert the original
-// router ranked j, the S sub-experts are scored by the mean absolute activation of their r gate
-// neurons (act: row slot(t, j) of the proxy activations, sub-expert n at columns n r .. n r + r - 1,
-// summed in ascending column order in fp32), and the best kappa[k_t][j] are taken, score
-// descending, equal scores to the smaller index.  Selected sub-experts are appended in rank
-// order with the expert's weight.
+// Sec. 3.2.2, training-free proxy gating.  One thread per (token, expert rank j).  For the expert
+// the original router ranked j, the S sub-experts are scored by the mean absolute activation of
+// their r gate neurons (act: row slot(t, j) of the proxy activations, sub-expert n at columns
+// n r .. n r + r - 1, summed in ascending column order in fp32), and the best kappa[k_t][j] are
+// taken, score descending, equal scores to the smaller index.  Selected sub-experts are
+// appended in rank order with the expert's weight: rank j writes at the sum of the ranks'
+// allocations before it, the last rank also pads the tail.
 template <typename ActT>
 __device__ __forceinline__ float act_abs(const ActT* p);
 template <>
@@ -492,24 +493,31 @@ __global__ __launch_bounds__(256) void proxy_select_kernel(
     const float* __restrict__ w0, const int32_t* __restrict__ slot0,
     const int32_t* __restrict__ k_tok, const int32_t* __restrict__ kappa, int32_t* __restrict__ ids,
     float* __restrict__ w, int32_t* __restrict__ hdr, int T, int S, int r, int m, int k_max) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= T) return;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= T * m) return;
+  const int t = idx / m, j = idx % m;
   const int k_cap = min(k_max, m * S);
   int kt = k_tok[t];
   if (kt < 0 || kt > k_cap) {
-    atomicOr(&hdr[HDR_FLAGS], 1);
+    if (j == 0) atomicOr(&hdr[HDR_FLAGS], 1);
     kt = kt < 0 ? 0 : k_cap;
   }
+  const int32_t* kap_row = kappa + (size_t)kt * m;
+  auto alloc = [&](int jj) {
+    const int e = ids0[(size_t)t * m + jj], slot = slot0[(size_t)t * m + jj];
+    int kap = kap_row[jj];
+    kap = kap < 0 ? 0 : (kap > S ? S : kap);
+    return (e < 0 || slot < 0) ? 0 : kap;
+  };
+  int pos = 0;
+  for (int jj = 0; jj < j; ++jj) pos += alloc(jj);
+  const int kap = alloc(j);
   int32_t* o = ids + (size_t)t * k_max;
   float* ow = w + (size_t)t * k_max;
-  int pos = 0;
-  const float inv_r = 1.0f / (float)r;
-  for (int j = 0; j < m; ++j) {
-    int kap = kappa[(size_t)kt * m + j];
-    kap = kap < 0 ? 0 : (kap > S ? S : kap);
-    const int e = ids0[(size_t)t * m + j], slot = slot0[(size_t)t * m + j];
-    if (e < 0 || slot < 0 || kap == 0) continue;
-    const ActT* a = act + (size_t)slot * act_ld;
+  if (kap > 0) {
+    const int e = ids0[idx];
+    const ActT* a = act + (size_t)slot0[idx] * act_ld;
+    const float inv_r = 1.0f / (float)r;
     float sc[PROXY_MAX_SUB];
 #pragma unroll
     for (int n = 0; n < PROXY_MAX_SUB; ++n) {
@@ -518,7 +526,7 @@ __global__ __launch_bounds__(256) void proxy_select_kernel(
         for (int c = 0; c < r; ++c) sum += act_abs<ActT>(a + n * r + c);
       sc[n] = n < S ? sum * inv_r : -1.0f;  // scores are >= 0: -1 marks taken or absent
     }
-    const float wj = w0[(size_t)t * m + j];
+    const float wj = w0[idx];
     for (int i = 0; i < kap && pos < k_max; ++i) {
       int best = 0;
 #pragma unroll
@@ -532,10 +540,11 @@ __global__ __launch_bounds__(256) void proxy_select_kernel(
       ++pos;
     }
   }
-  for (; pos < k_max; ++pos) {
-    o[pos] = -1;
-    ow[pos] = 0.0f;
-  }
+  if (j == m - 1)
+    for (; pos < k_max; ++pos) {
+      o[pos] = -1;
+      ow[pos] = 0.0f;
+    }
 }
 
 hipError_t launch_proxy_select(int dtype, const void* act, int act_ld, const int32_t* ids0,
@@ -544,10 +553,10 @@ hipError_t launch_proxy_select(int dtype, const void* act, int act_ld, const int
                                int S, int r, int m, int k_max, hipStream_t s) {
   if (T == 0) return hipSuccess;
   if (dtype == 0)
-    proxy_select_kernel<float><<<cdiv(T, 256), 256, 0, s>>>((const float*)act, act_ld, ids0, w0, slot0,
+    proxy_select_kernel<float><<<cdiv(T * m, 256), 256, 0, s>>>((const float*)act, act_ld, ids0, w0, slot0,
                                                            k_tok, kappa, ids, w, hdr, T, S, r, m, k_max);
   else
-    proxy_select_kernel<uint16_t><<<cdiv(T, 256), 256, 0, s>>>((const uint16_t*)act, act_ld, ids0, w0,
+    proxy_select_kernel<uint16_t><<<cdiv(T * m, 256), 256, 0, s>>>((const uint16_t*)act, act_ld, ids0, w0,
                                                               slot0, k_tok, kappa, ids, w, hdr, T, S, r,
                                                               m, k_max);
   return hipGetLastError();
