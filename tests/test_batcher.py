@@ -9,8 +9,8 @@ from paper_2510_19366_amd import binding as B
 
 N_GRID, K_GRID = [256, 1024, 4096, 16384], [8, 16, 24, 32]
 # T(n, k) of the fine layout measured on MI355X (ms per layer)
-MEASURED = [[0.374, 0.368, 0.372, 0.380], [0.382, 0.401, 0.421, 0.446],
-            [0.520, 0.610, 0.702, 0.882], [1.020, 1.548, 2.097, 2.641]]
+MEASURED = [[0.365, 0.363, 0.366, 0.375], [0.369, 0.389, 0.408, 0.429],
+            [0.488, 0.566, 0.664, 0.819], [1.006, 1.532, 2.069, 2.600]]
 
 
 def table(fn):
