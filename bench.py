@@ -48,6 +48,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (known traffic, for scaling "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--microbench", action="store_true",
+                    help="run the machine-peak microbenchmarks instead (matrix cores from registers "
+                         "and from LDS, LDS reads, operand streams, HBM copy) and print them as one "
+                         "JSON line")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -62,6 +66,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.microbench:
+        rows = B.moe_prism_microbench()
+        print(json.dumps({"microbench": [{"name": n, "value": v, "unit": u, "shader_mhz": m}
+                                         for n, v, u, m in rows]}))
+        return
     if args.route == "proxy":
         from paper_2510_19366_amd.compare_modes import request_budgets
         whole = W.config("c5a_s1_k8", T=args.tokens)

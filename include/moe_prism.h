@@ -291,6 +291,25 @@ MOE_PRISM_API int moe_prism_timing_enable(int on);
 MOE_PRISM_API int moe_prism_timing_select(uint32_t kernel_mask);
 MOE_PRISM_API int moe_prism_timing_read(float* ms, int32_t* calls);
 
+/*
+ * Machine-peak microbenchmarks (measurement only; no passage of the paper): what the
+ * matrix cores (operands in registers / fed from LDS, constant and random bf16 data),
+ * the LDS, the global->LDS and global->register paths (L2-, last-level-cache- and
+ * HBM-sized footprints) and an HBM streaming copy deliver on the current device, in
+ * loops shaped like the grouped-FFN kernels'.  Allocates and frees about 4 GiB of device
+ * memory of its own, runs on the null stream and synchronises.  results[max_results]
+ * (host) receives one record per test, *n_results (host) their number; shader_mhz is the
+ * average shader clock during the test (0 where not measured).
+ */
+typedef struct {
+  char name[64];
+  char unit[16];
+  double value;
+  double shader_mhz;
+} moe_prism_microbench_result;
+MOE_PRISM_API int moe_prism_microbench(int32_t max_results, moe_prism_microbench_result* results,
+                                       int32_t* n_results);
+
 MOE_PRISM_API const char* moe_prism_strerror(int code);
 
 #ifdef __cplusplus

@@ -23,7 +23,8 @@ EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_route_proxy", "moe_prism_layer_proxy", "moe_prism_plan_batches",
            "moe_prism_partition_greedy", "moe_prism_partition_objective", "moe_prism_partition_anneal",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
-           "moe_prism_timing_select", "moe_prism_timing_read", "moe_prism_strerror")
+           "moe_prism_timing_select", "moe_prism_timing_read", "moe_prism_microbench",
+           "moe_prism_strerror")
 
 
 class Shape(C.Structure):
@@ -329,6 +330,20 @@ def moe_prism_timing_read():
     calls = (C.c_int32 * n)()
     _check(lib().moe_prism_timing_read(ms, calls))
     return {k: (ms[i], calls[i]) for i, k in enumerate(KERNEL_NAMES)}
+
+
+class MicrobenchResult(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("unit", C.c_char * 16), ("value", C.c_double),
+                ("shader_mhz", C.c_double)]
+
+
+def moe_prism_microbench(max_results=64):
+    """Machine-peak microbenchmarks: list of (name, value, unit, shader MHz)."""
+    res = (MicrobenchResult * max_results)()
+    n = C.c_int32(0)
+    _check(lib().moe_prism_microbench(C.c_int32(max_results), res, C.byref(n)))
+    return [(res[i].name.decode(), res[i].value, res[i].unit.decode(), res[i].shader_mhz)
+            for i in range(n.value)]
 
 
 def to_device(wl, device="cuda"):
