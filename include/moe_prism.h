@@ -150,6 +150,25 @@ MOE_PRISM_API int moe_prism_layer(const moe_prism_shape* shape, const void* x, c
                     const void* w_down, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * moe_prism_layer for callers that cannot allocate device memory or pass a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels and results as moe_prism_layer, but the intermediates live in a
+ * device array of MOE_PRISM_STATIC_WS_BYTES that is part of the library's code object (one
+ * copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ * Shapes whose moe_prism_workspace_bytes() exceeds MOE_PRISM_STATIC_WS_BYTES are refused
+ * with MOE_PRISM_ERR_WORKSPACE before anything is launched.  Every call on a GPU uses
+ * that GPU's one array (whatever the stream), which keeps the previous call's contents;
+ * the kernels reset the words that must start at zero.  Calls that overlap in time on one
+ * GPU race: order them on one stream or with events.  The status word of this variant
+ * cannot be read back (budgets outside [0, k_max] are still clamped).
+ */
+#define MOE_PRISM_STATIC_WS_BYTES (64u << 20)
+MOE_PRISM_API int moe_prism_layer_static(const moe_prism_shape* shape, const void* x,
+                                         const void* w_router, const float* router_bias,
+                                         const int32_t* k_tok, const void* w_gate_up,
+                                         const void* w_down, void* out, void* stream);
+
+/*
  * Proxy-gate route mode (Sec. 3.2.2, "Training-Free Proxy Gating"): routing for a model
  * refactored WITHOUT training a new gate.  The original router w_router0 [N, d] (+ bias0 [N]
  * or NULL) scores the N original experts and its native top m are taken, ordered by logit,

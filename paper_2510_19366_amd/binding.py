@@ -20,6 +20,7 @@ KERNEL_NAMES = ("logits", "topk", "dispatch_count", "dispatch_scan", "dispatch_p
 
 EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
+           "moe_prism_layer_static",
            "moe_prism_route_proxy", "moe_prism_layer_proxy", "moe_prism_plan_batches",
            "moe_prism_partition_greedy", "moe_prism_partition_objective", "moe_prism_partition_anneal",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
@@ -154,6 +155,18 @@ def moe_prism_layer(shape, x, w_router, router_bias, k_tok, w_gate_up, w_down, w
     _check(lib().moe_prism_layer(C.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias),
                                  _ptr(k_tok), _ptr(w_gate_up), _ptr(w_down), _ptr(out), _ptr(ws),
                                  C.c_size_t(ws.numel()), _stream()))
+    return out
+
+
+STATIC_WS_BYTES = 64 << 20  # MOE_PRISM_STATIC_WS_BYTES
+
+
+def moe_prism_layer_static(shape, x, w_router, router_bias, k_tok, w_gate_up, w_down, out):
+    """moe_prism_layer on the library's own static device workspace: allocates nothing, so
+    `out` is the caller's."""
+    _check(lib().moe_prism_layer_static(C.byref(shape), _ptr(x), _ptr(w_router), _ptr(router_bias),
+                                        _ptr(k_tok), _ptr(w_gate_up), _ptr(w_down), _ptr(out),
+                                        _stream()))
     return out
 
 

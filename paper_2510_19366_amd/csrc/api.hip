@@ -331,17 +331,30 @@ int moe_prism_combine(const moe_prism_shape* shape, const void* y, const int32_t
   return MOE_PRISM_OK;
 }
 
-int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_router,
-                    const float* router_bias, const int32_t* k_tok, const void* w_gate_up,
-                    const void* w_down, void* out, void* ws, size_t ws_bytes, void* stream) {
-  MP_CHECK_SHAPE(shape);
-  if (w_router == nullptr || w_gate_up == nullptr || w_down == nullptr)
-    return MOE_PRISM_ERR_INVALID_ARG;
-  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || out == nullptr))
-    return MOE_PRISM_ERR_INVALID_ARG;
-  MP_CHECK_WS(shape, L, ws, ws_bytes);
-  char* w8 = static_cast<char*>(ws);
-  hipStream_t st = (hipStream_t)stream;
+// Workspace of moe_prism_layer_static: one file-scope device array per GPU, held until the
+// process ends.  `scratch` itself is only a host-side handle of the symbol; the device address
+// is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[MOE_PRISM_STATIC_WS_BYTES];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[64] = {};
+
+static int static_workspace(char** ws) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_PRISM_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr)
+      return MOE_PRISM_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *ws = static_cast<char*>(g_scratch_ptr[dev]);
+  return MOE_PRISM_OK;
+}
+
+static int layer_on(const moe_prism_shape* shape, const Layout& L, const void* x,
+                    const void* w_router, const float* router_bias, const int32_t* k_tok,
+                    const void* w_gate_up, const void* w_down, void* out, char* w8, hipStream_t st) {
   int32_t* ids = reinterpret_cast<int32_t*>(w8 + L.ids);
   float* w = reinterpret_cast<float*>(w8 + L.w);
   int32_t* cnt = reinterpret_cast<int32_t*>(w8 + L.cnt);
@@ -360,6 +373,36 @@ int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_r
   MP_LAUNCH(MOE_PRISM_K_COMBINE, launch_combine(shape->dtype, y, sl, w, k_tok, out, shape->T,
                                                 shape->d, shape->k_max, st));
   return MOE_PRISM_OK;
+}
+
+int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_router,
+                    const float* router_bias, const int32_t* k_tok, const void* w_gate_up,
+                    const void* w_down, void* out, void* ws, size_t ws_bytes, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (w_router == nullptr || w_gate_up == nullptr || w_down == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || out == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  return layer_on(shape, L, x, w_router, router_bias, k_tok, w_gate_up, w_down, out,
+                  static_cast<char*>(ws), (hipStream_t)stream);
+}
+
+int moe_prism_layer_static(const moe_prism_shape* shape, const void* x, const void* w_router,
+                           const float* router_bias, const int32_t* k_tok, const void* w_gate_up,
+                           const void* w_down, void* out, void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (w_router == nullptr || w_gate_up == nullptr || w_down == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || k_tok == nullptr || out == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  const Layout L = layout_of(shape);
+  if (L.total > (size_t)MOE_PRISM_STATIC_WS_BYTES) return MOE_PRISM_ERR_WORKSPACE;
+  char* w8 = nullptr;
+  int rc = static_workspace(&w8);
+  if (rc) return rc;
+  return layer_on(shape, L, x, w_router, router_bias, k_tok, w_gate_up, w_down, out, w8,
+                  (hipStream_t)stream);
 }
 
 int moe_prism_route_proxy(const moe_prism_shape* shape, const void* x, const void* w_router0,
@@ -462,7 +505,7 @@ const char* moe_prism_strerror(int code) {
     case MOE_PRISM_OK: return "ok";
     case MOE_PRISM_ERR_INVALID_ARG: return "invalid argument (null pointer, negative size, bad flag, unaligned workspace)";
     case MOE_PRISM_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (need d % 64 == 0, inter_sub % 32 == 0, k_max <= min(E, 1024), E <= 4096, int32 index range)";
-    case MOE_PRISM_ERR_WORKSPACE: return "workspace smaller than moe_prism_workspace_bytes()";
+    case MOE_PRISM_ERR_WORKSPACE: return "workspace smaller than moe_prism_workspace_bytes() (or, for moe_prism_layer_static, the shape needs more than MOE_PRISM_STATIC_WS_BYTES)";
     case MOE_PRISM_ERR_LAUNCH: return "HIP runtime error while enqueuing";
     default: return "unknown error";
   }
