@@ -110,7 +110,8 @@ def main():
     torch.cuda.synchronize()
     # timed region: HIP events around the dominant kernel only (the roofline figure); the other
     # kernels' durations come from a short pass of their own afterwards, outside the timing
-    B.moe_prism_timing_select(["ffn_gate_up"])
+    dom = "ffn_fused" if B.ffn_path(shape) == "fused" else "ffn_gate_up"
+    B.moe_prism_timing_select([dom])
     B.moe_prism_timing_enable(True)
     B.moe_prism_timing_read()
     torch.cuda.synchronize()
@@ -126,7 +127,7 @@ def main():
     torch.cuda.synchronize()
     kt_all = B.moe_prism_timing_read()
     B.moe_prism_timing_enable(False)
-    kt = {k: (kt[k] if k == "ffn_gate_up" else v) for k, v in kt_all.items()}
+    kt = {k: (kt[k] if k == dom else v) for k, v in kt_all.items()}
     flags, pairs = B.moe_prism_status(ws)
     assert flags == 0 and pairs == wl.pairs, (flags, pairs, wl.pairs)
 
@@ -136,17 +137,17 @@ def main():
     # dispatch, tile and gate-up kernels a second time on small shapes, so there the figures
     # are per-step sums
     if args.route == "proxy":
-        kern_ms = {k: v[0] / (args.steps if k == "ffn_gate_up" else min(args.steps, 10))
+        kern_ms = {k: v[0] / (args.steps if k == dom else min(args.steps, 10))
                    for k, v in kt.items()}
     else:
         kern_ms = {k: (v[0] / max(v[1], 1)) for k, v in kt.items()}
     P, d, Is, E = wl.pairs, wl.d, wl.inter_sub, wl.E
 
     # dominant kernel: the gate-up GEMM (2/3 of the FFN FLOPs); algorithmic FLOPs = 4*d*Is per pair
-    gu_flops = 4.0 * d * Is * P
     ffn_flops = 6.0 * d * Is * P
-    gu_tflops = gu_flops / (kern_ms["ffn_gate_up"] * 1e-3) / 1e12
-    ffn_ms = kern_ms["ffn_gate_up"] + kern_ms["ffn_down"] + kern_ms["ffn_tiles"]
+    gu_flops = ffn_flops if dom == "ffn_fused" else 4.0 * d * Is * P
+    gu_tflops = gu_flops / (kern_ms[dom] * 1e-3) / 1e12
+    ffn_ms = kern_ms["ffn_gate_up"] + kern_ms["ffn_down"] + kern_ms["ffn_tiles"] + kern_ms["ffn_fused"]
     ffn_tflops = ffn_flops / (ffn_ms * 1e-3) / 1e12
     el = 2 if wl.dtype == "bf16" else 4
     stage_bytes = {
@@ -174,7 +175,7 @@ def main():
         "ffn_mfma_util_pct": 100.0 * ffn_tflops / PEAK_BF16_TFLOPS,
         "ffn_tflops": ffn_tflops,
         "ffn_ms": ffn_ms,
-        "roofline": {"kernel": "ffn_gate_up", "bound": "mfma", "achieved": gu_tflops,
+        "roofline": {"kernel": dom, "bound": "mfma", "achieved": gu_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": gu_tflops / PEAK_BF16_TFLOPS,
                      "traffic": TRAFFIC_BYTES.get(wl.name)},

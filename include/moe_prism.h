@@ -305,7 +305,8 @@ MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t*
 #define MOE_PRISM_K_FFN_DOWN 7
 #define MOE_PRISM_K_COMBINE 8
 #define MOE_PRISM_K_PROXY_SELECT 9
-#define MOE_PRISM_N_KERNELS 10
+#define MOE_PRISM_K_FFN_FUSED 10 /* gate-up + SwiGLU + down in one kernel (narrow sub-experts) */
+#define MOE_PRISM_N_KERNELS 11
 MOE_PRISM_API int moe_prism_timing_enable(int on);
 MOE_PRISM_API int moe_prism_timing_select(uint32_t kernel_mask);
 MOE_PRISM_API int moe_prism_timing_read(float* ms, int32_t* calls);

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmoe_prism.so")
 
 KERNEL_NAMES = ("logits", "topk", "dispatch_count", "dispatch_scan", "dispatch_place",
-                "ffn_tiles", "ffn_gate_up", "ffn_down", "combine", "proxy_select")
+                "ffn_tiles", "ffn_gate_up", "ffn_down", "combine", "proxy_select", "ffn_fused")
 
 EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
@@ -156,6 +156,14 @@ def moe_prism_layer(shape, x, w_router, router_bias, k_tok, w_gate_up, w_down, w
                                  _ptr(k_tok), _ptr(w_gate_up), _ptr(w_down), _ptr(out), _ptr(ws),
                                  C.c_size_t(ws.numel()), _stream()))
     return out
+
+
+def ffn_path(shape):
+    """Which grouped-FFN kernels moe_prism_grouped_ffn / _layer launch for this shape: "fused"
+    (bf16, inter_sub in {64, 128, 192}, d >= 256, unless MOE_PRISM_FFN=split) or "split"."""
+    ok = (shape.dtype == 1 and shape.inter_sub in (64, 128, 192) and shape.d % 64 == 0
+          and shape.d >= 256 and shape.T * shape.d * 2 < 2 ** 32)
+    return "fused" if ok and os.environ.get("MOE_PRISM_FFN") != "split" else "split"
 
 
 STATIC_WS_BYTES = 64 << 20  # MOE_PRISM_STATIC_WS_BYTES

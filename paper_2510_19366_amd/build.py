@@ -6,7 +6,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_prism.so")
-SOURCES = ["route.hip", "dispatch.hip", "ffn.hip", "ffn_bf16.hip", "combine.hip", "microbench.hip", "batcher.hip", "partition.hip", "api.hip"]
+SOURCES = ["route.hip", "dispatch.hip", "ffn.hip", "ffn_bf16.hip", "ffn_fused_bf16.hip", "combine.hip", "microbench.hip", "batcher.hip", "partition.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -3,6 +3,8 @@
 // arithmetic is in the kernel files.
 #include "../../include/moe_prism.h"
 
+#include <cstdlib>
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -153,6 +155,15 @@ static int do_dispatch(const moe_prism_shape* s, const Layout& L, const int32_t*
   return MOE_PRISM_OK;
 }
 
+// The fused gate-up/SwiGLU/down kernel serves bf16 layers with narrow sub-experts; the
+// environment variable MOE_PRISM_FFN=split forces the two-kernel path (for A/B measurements
+// and so that tests reach both paths on the same shapes).
+static bool use_fused_ffn(const moe_prism_shape* s) {
+  if (s->dtype != MOE_PRISM_BF16 || !ffn_fused_supported(s->T, s->d, s->inter_sub)) return false;
+  const char* e = getenv("MOE_PRISM_FFN");
+  return !(e != nullptr && strcmp(e, "split") == 0);
+}
+
 static int do_ffn(const moe_prism_shape* s, const Layout& L, const void* x, const void* w_gu,
                   const void* w_dn, const int32_t* off, const int32_t* sorted_pair, void* y,
                   char* ws, hipStream_t st) {
@@ -162,6 +173,13 @@ static int do_ffn(const moe_prism_shape* s, const Layout& L, const void* x, cons
   void* h = ws + L.h;
   MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(off, tiles, hdr, E, L.max_mtiles, s->T * s->k_max, st));
   if (s->T == 0) return MOE_PRISM_OK;
+  if (use_fused_ffn(s)) {
+    MP_LAUNCH(MOE_PRISM_K_FFN_FUSED,
+              launch_ffn_fused_bf16((const uint16_t*)x, (const uint16_t*)w_gu, (const uint16_t*)w_dn,
+                                    sorted_pair, tiles, hdr, (uint16_t*)y, s->T, s->d, s->inter_sub,
+                                    s->k_max, L.max_mtiles, st));
+    return MOE_PRISM_OK;
+  }
   MP_LAUNCH(MOE_PRISM_K_FFN_GATE_UP,
             launch_ffn_gate_up(s->dtype, x, w_gu, sorted_pair, tiles, hdr, h, s->T, s->d, s->inter_sub,
                                s->k_max, L.max_mtiles, st));

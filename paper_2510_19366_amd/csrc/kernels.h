@@ -56,6 +56,13 @@ hipError_t launch_ffn_down(int dtype, const void* h, const void* w_dn, const MTi
                            int32_t* hdr, void* y, int d, int Is, int max_mtiles,
                            hipStream_t s);
 
+// fused gate-up -> SwiGLU -> down for narrow sub-experts (bf16); see ffn_fused_bf16.hip
+bool ffn_fused_supported(int T, int d, int Is);
+hipError_t launch_ffn_fused_bf16(const uint16_t* x, const uint16_t* w_gu, const uint16_t* w_dn,
+                                 const int32_t* sorted_pair, const MTile* tiles, int32_t* hdr,
+                                 uint16_t* y, int T, int d, int Is, int k_max, int max_mtiles,
+                                 hipStream_t s);
+
 hipError_t launch_combine(int dtype, const void* y, const int32_t* slot_of_pair, const float* w,
                           const int32_t* k_tok, void* out, int T, int d, int k_max, hipStream_t s);
 

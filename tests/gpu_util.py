@@ -50,3 +50,19 @@ def max_rel(got, ref):
     if den == 0:
         den = 1.0
     return float(np.abs(np.asarray(got, np.float64) - ref).max() / den) if ref.size else 0.0
+
+
+def row_rel(got, ref):
+    """Largest per-row error: max over rows of max|got_row - ref_row| / max|ref_row| (rows whose
+    reference is all zero must be exactly zero).  Catches a wrong low-magnitude row that the
+    whole-array figure of max_rel would hide."""
+    got = np.asarray(got, np.float64).reshape(len(ref), -1)
+    ref = np.asarray(ref, np.float64).reshape(len(ref), -1)
+    if ref.size == 0:
+        return 0.0
+    num = np.abs(got - ref).max(axis=1)
+    den = np.abs(ref).max(axis=1)
+    zero = den == 0
+    if np.any(num[zero] != 0):
+        return float("inf")
+    return float((num[~zero] / den[~zero]).max()) if np.any(~zero) else 0.0

@@ -9,7 +9,7 @@ import torch
 from oracle import oracle as O
 from paper_2510_19366_amd import binding as B
 from paper_2510_19366_amd import workloads as W
-from gpu_util import max_rel, run_layer, run_stages, to_np
+from gpu_util import max_rel, row_rel, run_layer, run_stages, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -68,6 +68,42 @@ def test_small_cases_full_oracle(dtype, case):
     check_against_oracle(wl, r, ref)
     out, _, _ = run_layer(wl, r["dev"], r["ws"])
     assert np.array_equal(to_np(out), r["out"])
+
+
+@pytest.mark.parametrize("path", ["fused", "split"])
+@pytest.mark.parametrize("case", [
+    # narrow sub-experts (Is in {64, 128, 192}, d >= 256): the fused gate-up/SwiGLU/down kernel.
+    # Several m-tiles per group with ragged tails, groups smaller than one wave's 32 rows, empty
+    # groups, one workgroup walking many tiles (more tiles than compute units in the last case),
+    # the shortest supported K (d = 256) and K lengths that are not powers of two
+    dict(T=900, d=256, N=5, S=4, Is=64, k_max=6),
+    dict(T=1200, d=512, N=3, S=4, Is=128, k_max=5),
+    dict(T=2000, d=320, N=6, S=4, Is=192, k_max=8),
+    dict(T=3, d=256, N=2, S=2, Is=192, k_max=4),
+    dict(T=700, d=704, N=40, S=4, Is=192, k_max=20),
+    dict(T=9000, d=256, N=64, S=4, Is=64, k_max=16),
+])
+def test_narrow_sub_experts_both_ffn_paths(case, path, monkeypatch):
+    # MOE_PRISM_FFN=split sends the same shapes through the gate-up and down kernels
+    monkeypatch.setenv("MOE_PRISM_FFN", "split" if path == "split" else "auto")
+    rng = np.random.default_rng(case["T"])
+    k = rng.integers(0, case["k_max"] + 1, size=case["T"]).astype(np.int32)
+    wl = W.make_workload("narrow", dtype="bf16", d=case["d"], n_experts=case["N"], n_sub=case["S"],
+                         inter_sub=case["Is"], req_tokens=[1] * case["T"], req_k=k,
+                         k_max=case["k_max"], seed=case["T"], bias_std=1.0, w_std=0.05)
+    r = run_stages(wl)
+    ref = O.layer_of(wl, return_all=True)
+    check_against_oracle(wl, r, ref)
+    assert row_rel(r["y"], ref["y"]) <= 4e-2 and row_rel(r["out"], ref["out"]) <= 4e-2
+    B.moe_prism_timing_enable(True)
+    B.moe_prism_timing_read()
+    out, _, _ = run_layer(wl, r["dev"], r["ws"])
+    calls = {k: v[1] for k, v in B.moe_prism_timing_read().items()}
+    B.moe_prism_timing_enable(False)
+    assert np.array_equal(to_np(out), r["out"])
+    # the intended kernels ran
+    assert (calls["ffn_fused"], calls["ffn_gate_up"], calls["ffn_down"]) == \
+        ((1, 0, 0) if path == "fused" else (0, 1, 1))
 
 
 def test_no_renormalize_and_repeated_rows():
