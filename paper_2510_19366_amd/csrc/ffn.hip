@@ -13,15 +13,36 @@ namespace mp {
 
 // ---------------------------------------------------------------- m-tile table
 constexpr int TILES_THREADS = 1024;
+
+// block-wide exclusive scan of one int per thread; returns the thread's prefix, *total the sum
+__device__ __forceinline__ int block_scan(int v, int32_t* wave_tot, int* total) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int incl = v;
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    int o = __shfl_up(incl, m, 64);
+    if (lane >= m) incl += o;
+  }
+  __syncthreads();  // wave_tot may still be read from the previous call
+  if (lane == 63) wave_tot[wv] = incl;
+  __syncthreads();
+  int wbase = 0, tot = 0;
+  for (int i = 0; i < TILES_THREADS / 64; ++i) {
+    if (i < wv) wbase += wave_tot[i];
+    tot += wave_tot[i];
+  }
+  *total = tot;
+  return wbase + incl - v;
+}
+
+// tiles[]: the m-tiles in group order (a group's tiles are contiguous)
 __global__ __launch_bounds__(TILES_THREADS) void ffn_tiles_kernel(const int32_t* __restrict__ off,
                                                                   MTile* __restrict__ tiles,
                                                                   int32_t* __restrict__ hdr, int E,
                                                                   int max_tiles, int n_rows) {
   __shared__ int32_t wave_tot[TILES_THREADS / 64];
-  __shared__ int32_t carry;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  if (tid == 0) carry = 0;
-  __syncthreads();
+  const int tid = threadIdx.x;
+  int carry = 0;  // tiles of the groups before this round (the same in every thread)
   for (int g0 = 0; g0 < E; g0 += TILES_THREADS) {
     int g = g0 + tid;
     int lo = 0, n = 0;
@@ -30,18 +51,9 @@ __global__ __launch_bounds__(TILES_THREADS) void ffn_tiles_kernel(const int32_t*
       n = off[g + 1] - lo;
       if (lo < 0 || n < 0 || lo > n_rows || n > n_rows - lo) n = 0;
     }
-    int nt = (n + FFN_BM - 1) / FFN_BM;
-    int incl = nt;
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-      int o = __shfl_up(incl, m, 64);
-      if (lane >= m) incl += o;
-    }
-    if (lane == 63) wave_tot[wv] = incl;
-    __syncthreads();
-    int wbase = 0;
-    for (int i = 0; i < wv; ++i) wbase += wave_tot[i];
-    int first = carry + wbase + incl - nt;
+    const int nt = (n + FFN_BM - 1) / FFN_BM;
+    int round_total = 0;
+    const int first = carry + block_scan(nt, wave_tot, &round_total);
     for (int i = 0; i < nt; ++i) {
       MTile t;
       t.g = g;
@@ -52,14 +64,17 @@ __global__ __launch_bounds__(TILES_THREADS) void ffn_tiles_kernel(const int32_t*
       t.pad[0] = t.pad[1] = t.pad[2] = 0;
       if (first + i < max_tiles) tiles[first + i] = t;
     }
-    __syncthreads();
-    if (tid == TILES_THREADS - 1) carry = first + nt;
-    __syncthreads();
+    carry += round_total;
   }
+  const int n_tiles = min(carry, max_tiles);
   if (tid == 0) {
-    hdr[HDR_MTILES] = min(carry, max_tiles);
+    hdr[HDR_MTILES] = n_tiles;
     hdr[HDR_DYN_GATE_UP] = 0;
     hdr[HDR_DYN_DOWN] = 0;
+    for (int i = 0; i < N_XCD; ++i) hdr[HDR_DYN_FUSED + i] = 0;
+    // more tiles than the table holds: only possible when a caller hands offsets that do not
+    // belong to this shape's pair capacity; never silent
+    if (carry > max_tiles) atomicOr(&hdr[HDR_FLAGS], 2);
   }
 }
 

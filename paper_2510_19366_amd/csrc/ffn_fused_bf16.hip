@@ -21,6 +21,8 @@
 // the rows it multiplies itself), so x needs no barrier.  Two stages are in flight while one
 // is multiplied.  vmcnt retires in issue order, so "everything but the operations this wave
 // issued in the previous iteration has landed" is one s_waitcnt with that count.
+#include <type_traits>
+
 #include "ffn_common.h"
 
 namespace mp {
@@ -36,6 +38,9 @@ constexpr int NSW = 4;    // weight ring slots
 constexpr int NSX = 3;    // x ring slots (per wave)
 constexpr int X_WAVE = 32 * 64;        // bytes of one wave's x stage: 32 rows x 32 K-elements
 constexpr int X_SLOT = 8 * X_WAVE;
+constexpr int EPI_WAVE = 1024;         // bytes of a wave's output staging: 16 rows x 32 columns
+constexpr int RUN = 32;   // consecutive tiles an XCD takes per turn
+constexpr int PD = 4;     // fragment reads in flight ahead of the MFMAs
 
 template <int IS>
 struct Cfg {
@@ -47,27 +52,51 @@ struct Cfg {
   static constexpr int ROW2 = IS * 2;      // bytes per weight row in phase 2
   static constexpr int OFF_X = NSW * W_SLOT;
   static constexpr int OFF_PAIR = OFF_X + NSX * X_SLOT;
-  static constexpr int LDS_BYTES = OFF_PAIR + 2 * BM * 4;
+  static constexpr int OFF_EPI = OFF_PAIR + 2 * BM * 4;  // 1 KiB per wave: output transposition
+  static constexpr int OFF_DYN = OFF_EPI + 8 * EPI_WAVE;  // two words: tile numbers drawn by wave 0
+  static constexpr int LDS_BYTES = OFF_DYN + 16;
   static_assert(LDS_BYTES <= 160 * 1024, "LDS per CU");
 };
 
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-// one wave-wide copy global -> LDS: lane i's 16 (4) bytes at base + voff land at lds + 16 i (4 i).
-// m0 is reserved by the compiler, so its value is put back.
-__device__ __forceinline__ void dma16(const void* base, uint32_t voff, uint32_t lds) {
+// Wave-wide copies global -> LDS: lane i's 16 (4) bytes at base + voff land at lds + 16 i (4 i).
+// N copies of one group go to consecutive KiB of LDS.  m0 carries the LDS address; it is
+// reserved by the compiler, so its value is put back.
+template <int N>
+__device__ __forceinline__ void dma16_group(const void* base, const uint32_t (&voff)[N], uint32_t lds) {
+  static_assert(N >= 1 && N <= 3, "copies per group");
   uint32_t keep;
-  asm volatile(
-      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 1\n\t"
-      "global_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
-      : "=&s"(keep)
-      : "v"(voff), "s"(base), "s"(lds)
-      : "memory");
+  if constexpr (N == 1) {
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(voff[0]), "s"(base), "s"(lds)
+        : "memory");
+  } else if constexpr (N == 2) {
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %4\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %3\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(voff[0]), "v"(voff[1]), "s"(base), "s"(lds)
+        : "memory", "scc");
+  } else {
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %4\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %4\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %3, %4\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(base), "s"(lds)
+        : "memory", "scc");
+  }
 }
 __device__ __forceinline__ void dma4(const void* base, uint32_t voff, uint32_t lds) {
   uint32_t keep;
   asm volatile(
-      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 1\n\t"
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\t"
       "global_load_lds_dword %1, %2\n\ts_mov_b32 m0, %0"
       : "=&s"(keep)
       : "v"(voff), "s"(base), "s"(lds)
@@ -83,20 +112,33 @@ __device__ __forceinline__ void store16(void* base, uint32_t voff, u32x4 v) {
   asm volatile("global_store_dwordx4 %0, %1, %2 offset:%3\n\ts_nop 1" ::"v"(voff), "v"(v), "s"(base), "n"(IMM)
                : "memory");
 }
-// until at most n of this wave's vector memory operations are pending (n is wave-uniform)
-__device__ __forceinline__ void wait_pending(int n) {
-#define MP_W(N) \
-  case N:       \
-    asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); \
-    break;
-  switch (n) {
-    MP_W(0) MP_W(1) MP_W(2) MP_W(3) MP_W(4) MP_W(5) MP_W(6) MP_W(7) MP_W(8) MP_W(9) MP_W(10)
-    MP_W(11) MP_W(12)
-    default:
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+// f(integral_constant<I>) for I = BEGIN .. END-1: a loop whose index can be a template argument
+template <int BEGIN, int END, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (BEGIN < END) {
+    f(std::integral_constant<int, BEGIN>{});
+    static_for<BEGIN + 1, END>(f);
   }
-#undef MP_W
 }
+// until at most n of this wave's vector memory operations are pending (n is wave-uniform, 0..12;
+// the count is an immediate of s_waitcnt, so n selects one of 13 instructions by bisection)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int LO, int HI>
+__device__ __forceinline__ void wait_bisect(int n) {
+  if constexpr (LO == HI) {
+    wait_vm<LO>();
+  } else {
+    constexpr int MID = (LO + HI + 1) / 2;
+    if (n >= MID)
+      wait_bisect<MID, HI>(n);
+    else
+      wait_bisect<LO, MID - 1>(n);
+  }
+}
+__device__ __forceinline__ void wait_pending(int n) { wait_bisect<0, 12>(n > 12 ? 0 : n); }
 __device__ __forceinline__ void barrier() {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
@@ -149,17 +191,32 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   const int lane = threadIdx.x & 63, wv = uni(threadIdx.x >> 6);
   const int S1 = d / 32, S2 = d / 64, ST = S1 + S2;
 
+  // Tiles are drawn at run time, one tile ahead of the one being multiplied, in table order
+  // (group-major: ragged tails, which only stream weights, stay interleaved with full tiles;
+  // drawing the heavy tiles first measured slower).  The workgroups of an XCD (workgroup b runs
+  // on XCD b % 8) share a cursor: the i-th tile an XCD draws is (i / RUN) * 8 RUN + xcd * RUN +
+  // i % RUN, so runs of RUN consecutive tiles, which mostly belong to one group, meet in one L2.
   const int n_tiles = hdr[HDR_MTILES];
-  const ItemRange ir = xcd_items(n_tiles);
-  const int n_my = ir.begin < ir.end ? (ir.end - ir.begin + ir.step - 1) / ir.step : 0;
-  if (n_my == 0) return;  // uniform over the workgroup
-  const int total = n_my * ST;
+  const int xcd = blockIdx.x % N_XCD;
+  int32_t* dyn_lds = reinterpret_cast<int32_t*>(smem + C::OFF_DYN);
+  auto draw = [&]() {  // one lane of the workgroup
+    const int i = atomicAdd(&hdr[HDR_DYN_FUSED + xcd], 1);
+    return (i / RUN) * (RUN * N_XCD) + xcd * RUN + (i % RUN);
+  };
+  if (threadIdx.x == 0) {
+    dyn_lds[0] = draw();
+    dyn_lds[1] = draw();
+  }
+  __syncthreads();
+  const int k0 = uni(dyn_lds[0]), k1 = uni(dyn_lds[1]);
+  if (k0 >= n_tiles) return;  // uniform over the workgroup
+  __syncthreads();            // dyn_lds is written again below
 
   const uint32_t lds0 = lds_addr(smem);
   const int32_t* pair_lds = reinterpret_cast<const int32_t*>(smem + C::OFF_PAIR);
 
-  auto load_hdr = [&](int my_idx, TileHdr& t) {
-    const MTile m = tiles[ir.begin + my_idx * ir.step];
+  auto load_hdr = [&](int k, TileHdr& t) {
+    const MTile m = tiles[k];
     t.g = uni(m.g);
     t.row0 = uni(m.row0);
     t.rows = uni(m.rows);
@@ -167,7 +224,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
   // ---- per-lane copy offsets that never change
   // phase 1 weights: piece pc = 16 ring rows; ring row lr holds block row lr & 31 of block lr >> 5
-  uint32_t voff_w1[WPW], voff_w2[WPW];
+  uint32_t voff_w1[WPW];
 #pragma unroll
   for (int j = 0; j < WPW; ++j) {
     const int pc = wv * WPW + j;
@@ -175,30 +232,28 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const int rr = lr & 31, neuron = (lr >> 5) * 16 + (rr & 15);
     const int grow = (rr >> 4) ? IS + neuron : neuron;
     voff_w1[j] = (uint32_t)grow * (uint32_t)d * 2u + (uint32_t)((pos ^ f1(lr)) * 16);
-    // phase 2 weights: piece = 64 consecutive 16-byte positions of a [64 x CPR] slot
-    const int p = pc * 64 + lane, r2 = p / C::CPR, pos2 = p % C::CPR;
-    voff_w2[j] = (uint32_t)r2 * C::ROW2 + (uint32_t)((pos2 ^ f2<IS>(r2)) * 16);
   }
-  // ---- per-lane fragment read offsets (bytes inside a slot)
-  const int fr = lane & 31, fh = lane >> 5;
-  // phase 1: row wrow_gu(fr) (+ 32 per block), chunk 2 ks + fh
-  uint32_t rd_w1[2], rd_x[2];
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    const int r = wrow_gu(fr), c = 2 * ks + fh;
-    rd_w1[ks] = (uint32_t)(r * 64 + ((c ^ f1(r)) * 16));
-    rd_x[ks] = (uint32_t)(fr * 64 + ((c ^ f1(fr)) * 16));
-  }
-  const int r2rd = wrow_dn(fr);
-  const uint32_t rd_w2_row = (uint32_t)r2rd * C::ROW2;
-  const int f2rd = f2<IS>(r2rd);
+  // phase 2 weights: piece = 64 consecutive 16-byte positions of a [64 x CPR] slot; computed
+  // when needed (registers are scarcest in phase 1, which does not use these)
+  auto voff_w2 = [&](int j) {
+    const int p = (wv * WPW + j) * 64 + lane, r2 = p / C::CPR, pos2 = p % C::CPR;
+    return (uint32_t)r2 * C::ROW2 + (uint32_t)((pos2 ^ f2<IS>(r2)) * 16);
+  };
+  // A copy of the lane id that the optimiser cannot see through: per-lane constants of one
+  // phase are derived from it at the start of that phase, so they do not occupy registers
+  // during the other (phase 1 runs at the register limit).
+  auto opaque_lane = [&]() {
+    int l = lane;
+    asm volatile("" : "+v"(l));
+    return l;
+  };
 
-  // x offsets of the rows this lane copies (2 pieces of 16 rows), for the current / next tile
-  uint32_t xoff_cur[2], xoff_nxt[2];
+  // x offsets of the rows this lane copies (2 pieces of 16 rows) from a tile's slot list in LDS
   auto x_offsets = [&](int parity, uint32_t (&xo)[2]) {
+    const int l = opaque_lane();
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int lr = j * 16 + (lane >> 2), pos = lane & 3;
+      const int lr = j * 16 + (l >> 2), pos = l & 3;
       int tok = pair_lds[parity * BM + wv * 32 + lr] / k_max;
       tok = min(max(tok, 0), T - 1);
       xo[j] = (uint32_t)tok * (uint32_t)d * 2u + (uint32_t)((pos ^ f1(lr)) * 16);
@@ -206,180 +261,299 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   };
   auto fetch_pairs = [&](const TileHdr& t, int parity) -> int {  // waves 0..3, 64 rows each
     if (wv >= 4) return 0;
-    const int r = max(min(wv * 64 + lane, t.rows - 1), 0);
+    const int r = max(min(wv * 64 + opaque_lane(), t.rows - 1), 0);
     dma4(sorted_pair + t.row0, (uint32_t)r * 4u, lds0 + C::OFF_PAIR + (uint32_t)(parity * BM + wv * 64) * 4u);
     return 1;
   };
-  // copies of weight stage s of a tile into ring slot `slot`
-  auto issue_w = [&](const TileHdr& t, int s, int slot) -> int {
-    const uint32_t dst = lds0 + (uint32_t)slot * C::W_SLOT + (uint32_t)(wv * WPW) * 1024u;
-    if (s < S1) {
-      const uint16_t* base = w_gu + (size_t)t.g * (2 * IS) * d + (size_t)s * 32;
+
+  // ---- prologue: tile 0's slot list
+  TileHdr cur, nxt;
+  load_hdr(k0, cur);
+  nxt = cur;
+  bool has_next = k1 < n_tiles;
+  if (has_next) load_hdr(k1, nxt);
+  int k_after = n_tiles;  // the tile after `nxt` (>= n_tiles: none)
+  int par = 0;            // which half of the slot-list buffer holds the current tile's entries
+  fetch_pairs(cur, 0);
+  wait_vm<0>();
+  barrier();
+
+  // ---- producers.  Each keeps a running global pointer and LDS address and counts the stages
+  // left in its phase; they run ahead of the multiplying code across phase and tile borders
+  // (the next tile's header `nxt` is known a whole tile ahead).
+  // weights: stage q + 3
+  const uint16_t* pw_ptr = w_gu + (size_t)cur.g * (2 * IS) * d;
+  int pw_g = cur.g, pw_phase = 0, pw_cnt = S1;
+  bool pw_on = true;  // false once the last tile's last stage has been issued
+  const uint32_t pw_dst0 = lds0 + (uint32_t)(wv * WPW) * 1024u;
+  uint32_t pw_dst = pw_dst0;
+  auto produce_w = [&]() -> int {
+    if (!pw_on) return 0;
+    if (pw_phase) {
+      uint32_t vo[WPW];
 #pragma unroll
-      for (int j = 0; j < WPW; ++j) dma16(base, voff_w1[j], dst + j * 1024u);
+      for (int j = 0; j < WPW; ++j) vo[j] = voff_w2(j);
+      dma16_group<WPW>(pw_ptr, vo, pw_dst);
+      pw_ptr += 64 * IS;
     } else {
-      const uint16_t* base = w_dn + ((size_t)t.g * d + (size_t)(s - S1) * 64) * IS;
-#pragma unroll
-      for (int j = 0; j < WPW; ++j) dma16(base, voff_w2[j], dst + j * 1024u);
+      dma16_group<WPW>(pw_ptr, voff_w1, pw_dst);
+      pw_ptr += 32;
+    }
+    pw_dst = pw_dst + C::W_SLOT == pw_dst0 + NSW * C::W_SLOT ? pw_dst0 : pw_dst + C::W_SLOT;
+    if (--pw_cnt == 0) {
+      if (pw_phase == 0) {  // on to the down weights of the same group
+        pw_phase = 1;
+        pw_cnt = S2;
+        pw_ptr = w_dn + (size_t)pw_g * d * IS;
+      } else if (has_next) {  // on to the next tile
+        pw_phase = 0;
+        pw_cnt = S1;
+        pw_g = nxt.g;
+        pw_ptr = w_gu + (size_t)pw_g * (2 * IS) * d;
+      } else {
+        pw_on = false;
+      }
     }
     return WPW;
   };
-  // copies of this wave's rows of x stage s (phase 1 only) into its private ring slot
-  auto issue_x = [&](const TileHdr& t, const uint32_t (&xo)[2], int s, int slot) -> int {
-    if (s >= S1 || t.rows <= wv * 32) return 0;
-    const uint32_t dst = lds0 + C::OFF_X + (uint32_t)slot * X_SLOT + (uint32_t)wv * X_WAVE;
-    const uint16_t* base = x + (size_t)s * 32;
-    dma16(base, xo[0], dst);
-    dma16(base, xo[1], dst + 1024u);
-    return 2;
-  };
-
-  // ---- prologue: tile 0's slot list, then the first stages
-  TileHdr cur, nxt;
-  load_hdr(0, cur);
-  nxt = cur;
-  if (n_my > 1) load_hdr(1, nxt);
-  fetch_pairs(cur, 0);
-  wait_pending(0);
-  barrier();
-  x_offsets(0, xoff_cur);
-  xoff_nxt[0] = xoff_cur[0];
-  xoff_nxt[1] = xoff_cur[1];
-
-  // producer cursors: stage inside its tile and whether that tile is `nxt`
-  int pw_s = 0, pw_next = 0, pw_slot = 0;  // next weight stage to issue
-  int px_s = 0, px_next = 0, px_slot = 0;  // next x stage to issue
-  int pw_q = 0, px_q = 0;                  // their global stage numbers
-  auto produce_w = [&]() -> int {
-    if (pw_q >= total) return 0;
-    const int n = issue_w(pw_next ? nxt : cur, pw_s, pw_slot);
-    ++pw_q;
-    pw_slot = pw_slot + 1 == NSW ? 0 : pw_slot + 1;
-    if (++pw_s == ST) {
-      pw_s = 0;
-      pw_next = 1;
+  // x: stage q + 2, phase-1 stages only, and only for a wave that has rows in the tile.  The
+  // cursor leaves a tile only while the multiplying code is in that tile's phase 2, which is
+  // where the next tile's offsets `xo_next` live.
+  uint32_t xoff[2];
+  x_offsets(0, xoff);
+  const uint16_t* px_ptr = x;
+  int px_s = 0;
+  bool px_on = true;
+  bool px_act = cur.rows > wv * 32;
+  const uint32_t px_dst0 = lds0 + C::OFF_X + (uint32_t)wv * X_WAVE;
+  uint32_t px_dst = px_dst0;
+  auto produce_x = [&](const uint32_t* xo_next) -> int {
+    if (!px_on) return 0;
+    int n = 0;
+    if (px_s < S1 && px_act) {
+      dma16_group<2>(px_ptr, xoff, px_dst);
+      n = 2;
+    }
+    px_ptr += 32;
+    px_dst = px_dst + X_SLOT == px_dst0 + NSX * X_SLOT ? px_dst0 : px_dst + X_SLOT;
+    if (++px_s == ST && xo_next != nullptr) {
+      if (has_next) {  // on to the next tile
+        px_s = 0;
+        px_ptr = x;
+        px_act = nxt.rows > wv * 32;
+        xoff[0] = xo_next[0];
+        xoff[1] = xo_next[1];
+      } else {
+        px_on = false;
+      }
     }
     return n;
   };
-  auto produce_x = [&]() -> int {
-    if (px_q >= total) return 0;
-    const int n = px_next ? issue_x(nxt, xoff_nxt, px_s, px_slot) : issue_x(cur, xoff_cur, px_s, px_slot);
-    ++px_q;
-    px_slot = px_slot + 1 == NSX ? 0 : px_slot + 1;
-    if (++px_s == ST) {
-      px_s = 0;
-      px_next = 1;
-    }
-    return n;
-  };
+  // Stage numbering: q counts the stages this workgroup walks.  Per iteration q a wave
+  //   (a) multiplies stage q (W(q) was published by the barrier of iteration q - 1, x(q) is its own),
+  //   (b) passes barrier(q): every wave has finished reading W(q-1), and W(q+1) is published,
+  //   (c) issues its copies of x(q+2) and W(q+3) (into the slots of x(q-1), W(q-1)),
+  //   (d) waits until everything it issued before (c) has landed, except the output stores of
+  //       the previous iteration: that is x(q+1) and its part of W(q+2) (issued in iteration
+  //       q - 1).  From here on the fragments of stage q + 1 may be read.
+  // (b)-(d) sit between MFMAs of (a) so that their scalar work and waiting hide behind them.
   produce_w();  // W(0)
   produce_w();  // W(1)
-  produce_x();  // x(0)
-  int cnt_prev = produce_w();  // W(2)   } the group an iteration would have issued
-  cnt_prev += produce_x();     // x(1)   }
-  wait_pending(cnt_prev);      // W(0), W(1), x(0) have landed
+  produce_x(nullptr);  // x(0)
+  {
+    int c0 = produce_x(nullptr);  // x(1)  } what iteration -1 would have issued
+    c0 += produce_w();            // W(2)  }
+    wait_pending(c0);             // W(0), W(1), x(0) have landed
+  }
   barrier();
 
-  int tile_i = 0, c_wslot = 0, c_xslot = 0;
-  // head of every iteration (stage s of the current tile): everything this wave issued before
-  // the previous iteration has landed, i.e. its part of W(q+1), and x(q); the barrier
-  // publishes W(q+1) and frees the slot of W(q-1); then the copies of W(q+3) and x(q+2) go out
-  auto head = [&](int s) -> int {
-    wait_pending(cnt_prev);
-    barrier();
-    int cnt = produce_w();
-    cnt += produce_x();
-    if (s == 1 && tile_i + 1 < n_my) cnt += fetch_pairs(nxt, (tile_i + 1) & 1);
-    if (s == S1 && tile_i + 1 < n_my) x_offsets((tile_i + 1) & 1, xoff_nxt);
-    return cnt;
+  // wave 0 draws the tile after `nxt` early in a tile (its wait for the returned number drains
+  // that wave's copies once per tile); every wave picks the number up two barriers later
+  auto sched_hook = [&](int s) {
+    if (s == 0 && has_next && threadIdx.x == 0) dyn_lds[0] = draw();
+    if (s == 2 && has_next) k_after = uni(dyn_lds[0]);
   };
+  uint32_t c_w = 0, c_x = 0;  // byte offsets of the ring slots of stage q
+  int n_allow = 0;  // operations that may still be pending at (d): last iteration's output stores + (c)
+  auto step_d = [&]() {
+    wait_pending(n_allow);
+    n_allow = 0;
+  };
+  auto next_w = [&](uint32_t c) { return c + C::W_SLOT == NSW * C::W_SLOT ? 0u : c + C::W_SLOT; };
+  auto next_x = [&](uint32_t c) { return c + X_SLOT == NSX * X_SLOT ? 0u : c + X_SLOT; };
+  constexpr int STEPS = 2 * NBLK;          // MFMAs per wave and stage, both phases
+  constexpr int B_STEP = 1;                // (b), (c) after this step
+  constexpr int WT_STEP = STEPS - PD - 2;  // (d) after this step, before the first read of stage q + 1
+  constexpr int XA0_STEP = WT_STEP > NBLK - 1 ? WT_STEP : NBLK - 1;  // x fragment 0 is free and x(q+1) landed
+  static_assert(WT_STEP > B_STEP, "order of the in-stage hooks");
 
-  for (; tile_i < n_my; ++tile_i) {
-    const bool active = cur.rows > wv * 32;
-    bf16x8 hfrag[NBLK];
-    {
-      // ---- phase 1: acc1[blk] += W-block(blk) x-rows^T, 32 K-elements per stage
-      f32x16 acc1[NBLK];
+  for (;;) {
+    if (cur.rows <= wv * 32) {
+      // a wave whose 32 rows lie beyond the tile's rows only takes part in the copies and barriers
+      uint32_t xo_next[2] = {xoff[0], xoff[1]};
+      for (int s = 0; s < ST; ++s) {
+        barrier();
+        n_allow += produce_x(xo_next);
+        n_allow += produce_w();
+        sched_hook(s);
+        if (s == 1 && has_next) n_allow += fetch_pairs(nxt, par ^ 1);
+        if (s == S1 && has_next) x_offsets(par ^ 1, xo_next);
+        step_d();
+        c_w = next_w(c_w);
+        c_x = next_x(c_x);
+      }
+    } else {
+      bf16x8 hfrag[NBLK];
+      {
+        // ---- phase 1: acc1[blk] += W-block(blk) x-rows^T, 32 K-elements (2 K steps) per stage.
+        // The fragment of step i + PD is read right after the MFMA of step i is issued (the
+        // scheduling barriers keep that order), and the stream of reads runs on into the next
+        // stage (after the last stage of the phase it reads a slot whose values are not used).
+        const int l = opaque_lane(), fr = l & 31, fh = l >> 5;
+        // fragment read offsets: row wrow_gu(fr) (+ 32 per block), chunk 2 ks + fh
+        uint32_t rd_w1[2], rd_x[2];
 #pragma unroll
-      for (int b = 0; b < NBLK; ++b)
+        for (int ks = 0; ks < 2; ++ks) {
+          const int r = wrow_gu(fr), c = 2 * ks + fh;
+          rd_w1[ks] = (uint32_t)(r * 64 + ((c ^ f1(r)) * 16));
+          rd_x[ks] = (uint32_t)(C::OFF_X + wv * X_WAVE + fr * 64 + ((c ^ f1(fr)) * 16));
+        }
+        auto rd_w1f = [&](uint32_t slot, int step) {
+          return *reinterpret_cast<const bf16x8*>(smem + slot + rd_w1[step / NBLK] + (step % NBLK) * 2048);
+        };
+        auto rd_xf = [&](uint32_t slot, int ks) {
+          return *reinterpret_cast<const bf16x8*>(smem + slot + rd_x[ks]);
+        };
+        f32x16 acc1[NBLK];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc1[b][v] = 0.0f;
-      for (int s = 0; s < S1; ++s) {
-        cnt_prev = head(s);
-        if (active) {
-          const unsigned char* wslot = smem + c_wslot * C::W_SLOT;
-          const unsigned char* xs = smem + C::OFF_X + c_xslot * X_SLOT + wv * X_WAVE;
+        for (int b = 0; b < NBLK; ++b)
 #pragma unroll
-          for (int ks = 0; ks < 2; ++ks) {
-            const bf16x8 xa = *reinterpret_cast<const bf16x8*>(xs + rd_x[ks]);
+          for (int v = 0; v < 16; ++v) acc1[b][v] = 0.0f;
+        bf16x8 xa[2], wf[PD];
+        xa[0] = rd_xf(c_x, 0);
 #pragma unroll
-            for (int b = 0; b < NBLK; ++b) {
-              const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wslot + rd_w1[ks] + b * 2048);
-              acc1[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xa, acc1[b], 0, 0, 0);
+        for (int i = 0; i < PD; ++i) wf[i] = rd_w1f(c_w, i);
+        xa[1] = rd_xf(c_x, 1);
+        for (int s = 0; s < S1; ++s) {
+          const uint32_t nw = next_w(c_w), nx = next_x(c_x);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int i = 0; i < STEPS; ++i) {
+            acc1[i % NBLK] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i % PD], xa[i / NBLK], acc1[i % NBLK], 0, 0, 0);
+            wf[i % PD] = i + PD < STEPS ? rd_w1f(c_w, i + PD) : rd_w1f(nw, i + PD - STEPS);
+            if (i == XA0_STEP + 1) xa[0] = rd_xf(nx, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i == B_STEP) {
+              barrier();
+              n_allow += produce_x(nullptr);  // stays inside this tile's stages
+              n_allow += produce_w();
+              sched_hook(s);
+              if (s == 1 && has_next) n_allow += fetch_pairs(nxt, par ^ 1);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            if (i == WT_STEP) {
+              step_d();
+              __builtin_amdgcn_sched_barrier(0);
             }
           }
+          xa[1] = rd_xf(nx, 1);
+          c_w = nw;
+          c_x = nx;
         }
-        c_wslot = c_wslot + 1 == NSW ? 0 : c_wslot + 1;
-        c_xslot = c_xslot + 1 == NSX ? 0 : c_xslot + 1;
-      }
-      // ---- SwiGLU: gate/up accumulators -> the bf16 K-step fragments of phase 2
+        // ---- SwiGLU: gate/up accumulators -> the bf16 K-step fragments of phase 2, block by
+        // block (16 accumulator registers become 4), before anything of phase 2 is read
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int b = 0; b < NBLK; ++b) {
-        const f32x16 v = acc1[b];
-        const uint4 pk = make_uint4(pack_bf16x2(silu_mul(v[0], v[8]), silu_mul(v[1], v[9])),
-                                    pack_bf16x2(silu_mul(v[2], v[10]), silu_mul(v[3], v[11])),
-                                    pack_bf16x2(silu_mul(v[4], v[12]), silu_mul(v[5], v[13])),
-                                    pack_bf16x2(silu_mul(v[6], v[14]), silu_mul(v[7], v[15])));
-        hfrag[b] = __builtin_bit_cast(bf16x8, pk);
+        for (int b = 0; b < NBLK; ++b) {
+          const f32x16 v = acc1[b];
+          const uint4 pk = make_uint4(pack_bf16x2(silu_mul(v[0], v[8]), silu_mul(v[1], v[9])),
+                                      pack_bf16x2(silu_mul(v[2], v[10]), silu_mul(v[3], v[11])),
+                                      pack_bf16x2(silu_mul(v[4], v[12]), silu_mul(v[5], v[13])),
+                                      pack_bf16x2(silu_mul(v[6], v[14]), silu_mul(v[7], v[15])));
+          hfrag[b] = __builtin_bit_cast(bf16x8, pk);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-    }
-    // ---- phase 2: 64 output columns per stage, K = Is from the register-resident h fragments
-    const int row = wv * 32 + fr;
-    const uint32_t vo = (uint32_t)row * (uint32_t)d * 2u + (uint32_t)fh * 32u;
-    for (int s2 = 0; s2 < S2; ++s2) {
-      int cnt = head(S1 + s2);
-      if (active) {
-        const unsigned char* wslot = smem + c_wslot * C::W_SLOT;
+      // ---- phase 2: 64 output columns per stage (2 blocks of 32), K = Is (NBLK K steps) from
+      // the register-resident h fragments; step i = K step i >> 1 of block i & 1
+      const int l = opaque_lane(), fr = l & 31, fh = l >> 5;
+      const int r2rd = wrow_dn(fr), f2rd = f2<IS>(r2rd);
+      const uint32_t rd_w2_row = (uint32_t)r2rd * C::ROW2;
+      auto rd_w2f = [&](uint32_t slot, int step) {
+        const uint32_t co = (uint32_t)(((2 * (step >> 1) + fh) ^ f2rd) * 16);
+        return *reinterpret_cast<const bf16x8*>(smem + slot + rd_w2_row + (step & 1) * 32 * C::ROW2 + co);
+      };
+      // Output staging: a lane ends a stage with 16 consecutive columns of ONE slot row per
+      // block, and neighbouring lanes hold different rows, 2*d bytes apart; stored like that
+      // every lane's 16 bytes are a memory access of their own (measured: 64 accesses per
+      // instruction, and the stores alone keep the address unit busy for a quarter of the
+      // kernel).  So 16 rows x 32 columns at a time go through 1 KiB of wave-private LDS and are
+      // stored with 4 adjacent lanes covering 64 contiguous bytes of a row.
+      unsigned char* epi = smem + C::OFF_EPI + wv * EPI_WAVE;
+      const uint32_t epi_wr = (uint32_t)((fr & 15) * 64 + fh * 32);
+      const uint32_t epi_rd = (uint32_t)l * 16u;  // row l >> 2 of the 16, 16-byte chunk l & 3
+      const int srow = wv * 32 + (l >> 2);        // + 16 for the second half of the wave's rows
+      const uint32_t vo = (uint32_t)srow * (uint32_t)d * 2u + (uint32_t)(l & 3) * 16u;
+      const uint32_t vo16 = vo + 16u * (uint32_t)d * 2u;
+      uint16_t* ybase = y + (size_t)cur.row0 * d;
+      uint32_t xo_next[2] = {xoff[0], xoff[1]};
+      bf16x8 wd[PD];
+#pragma unroll
+      for (int i = 0; i < PD; ++i) wd[i] = rd_w2f(c_w, i);
+      for (int s2 = 0; s2 < S2; ++s2) {
+        const uint32_t nw = next_w(c_w);
         f32x16 acc2[2];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int v = 0; v < 16; ++v) acc2[b][v] = 0.0f;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < NBLK; ++ks) {
-          const uint32_t co = (uint32_t)(((2 * ks + fh) ^ f2rd) * 16);
-#pragma unroll
-          for (int b = 0; b < 2; ++b) {
-            const bf16x8 wd = *reinterpret_cast<const bf16x8*>(wslot + rd_w2_row + b * 32 * C::ROW2 + co);
-            acc2[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd, hfrag[ks], acc2[b], 0, 0, 0);
+        for (int i = 0; i < STEPS; ++i) {
+          acc2[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd[i % PD], hfrag[i >> 1], acc2[i & 1], 0, 0, 0);
+          wd[i % PD] = i + PD < STEPS ? rd_w2f(c_w, i + PD) : rd_w2f(nw, i + PD - STEPS);
+          __builtin_amdgcn_sched_barrier(0);
+          if (i == B_STEP) {
+            barrier();
+            n_allow += produce_x(xo_next);
+            n_allow += produce_w();
+            if (s2 == 0 && has_next) x_offsets(par ^ 1, xo_next);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (i == WT_STEP) {
+            step_d();
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
         // lane (row fr, half fh) holds columns 64 s2 + 32 b + 16 fh + 0..15 of slot row 32 wv + fr
-        if (row < cur.rows) {
-          uint16_t* ybase = y + (size_t)cur.row0 * d + (size_t)s2 * 64;
-          const f32x16 a0 = acc2[0], a1 = acc2[1];
-          store16<0>(ybase, vo, u32x4{pack_bf16x2(a0[0], a0[1]), pack_bf16x2(a0[2], a0[3]),
-                                           pack_bf16x2(a0[4], a0[5]), pack_bf16x2(a0[6], a0[7])});
-          store16<16>(ybase, vo, u32x4{pack_bf16x2(a0[8], a0[9]), pack_bf16x2(a0[10], a0[11]),
-                                            pack_bf16x2(a0[12], a0[13]), pack_bf16x2(a0[14], a0[15])});
-          store16<64>(ybase, vo, u32x4{pack_bf16x2(a1[0], a1[1]), pack_bf16x2(a1[2], a1[3]),
-                                            pack_bf16x2(a1[4], a1[5]), pack_bf16x2(a1[6], a1[7])});
-          store16<80>(ybase, vo, u32x4{pack_bf16x2(a1[8], a1[9]), pack_bf16x2(a1[10], a1[11]),
-                                            pack_bf16x2(a1[12], a1[13]), pack_bf16x2(a1[14], a1[15])});
-        }
-        cnt += 4;  // row 32 wv of an active wave is valid, so the four stores were issued
+        static_for<0, 4>([&](auto Q) {
+          constexpr int b = decltype(Q)::value >> 1, hf = decltype(Q)::value & 1;
+          const f32x16 a = acc2[b];
+          if ((fr >> 4) == hf) {
+            *reinterpret_cast<uint4*>(epi + epi_wr) = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]),
+                                                                pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+            *reinterpret_cast<uint4*>(epi + epi_wr + 16) = make_uint4(pack_bf16x2(a[8], a[9]), pack_bf16x2(a[10], a[11]),
+                                                                     pack_bf16x2(a[12], a[13]), pack_bf16x2(a[14], a[15]));
+          }
+          const uint4 q = *reinterpret_cast<const uint4*>(epi + epi_rd);
+          if (srow + 16 * hf < cur.rows) store16<b * 64>(ybase, hf ? vo16 : vo, u32x4{q.x, q.y, q.z, q.w});
+        });
+        // Stores that were certainly issued (a lower bound keeps the wait at (d) safe): row 32 wv
+        // of this wave is valid, rows 32 wv + 16.. only if the tile has that many.  They may
+        // stay pending through the next iteration's (d).
+        n_allow = cur.rows > wv * 32 + 16 ? 4 : 2;
+        ybase += 64;
+        c_w = nw;
+        c_x = next_x(c_x);  // the x ring turns with every stage
       }
-      cnt_prev = cnt;
-      c_wslot = c_wslot + 1 == NSW ? 0 : c_wslot + 1;
-      c_xslot = c_xslot + 1 == NSX ? 0 : c_xslot + 1;  // the x ring turns with every stage
     }
     // ---- next tile
+    if (!has_next) break;
     cur = nxt;
-    xoff_cur[0] = xoff_nxt[0];
-    xoff_cur[1] = xoff_nxt[1];
-    pw_next = 0;
-    px_next = 0;
-    if (tile_i + 2 < n_my) load_hdr(tile_i + 2, nxt);
+    par ^= 1;
+    has_next = k_after < n_tiles;
+    if (has_next) load_hdr(k_after, nxt);
+    k_after = n_tiles;
   }
 }
 

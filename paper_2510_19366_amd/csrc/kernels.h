@@ -8,7 +8,8 @@ namespace mp {
 
 // Workspace header: int32 words at the start of ws.
 // HDR_DYN_*: cursors of the FFN kernels' work pools (cleared with the m-tile table)
-enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_DYN_GATE_UP = 3, HDR_DYN_DOWN = 4, HDR_WORDS = 64 };
+// HDR_DYN_FUSED .. +7: the fused FFN kernel's per-XCD tile cursors
+enum { HDR_FLAGS = 0, HDR_PAIRS = 1, HDR_MTILES = 2, HDR_DYN_GATE_UP = 3, HDR_DYN_DOWN = 4, HDR_DYN_FUSED = 8, HDR_WORDS = 64 };
 
 constexpr int FFN_BM = 256;  // rows of one m-tile of the grouped GEMMs
 

@@ -219,6 +219,37 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const char* __restrict_
   if (blockIdx.x == 0 && threadIdx.x == 0) *clk = Clk{c1 - c0, r1 - r0};
 }
 
+// ------------------------------------------------------------------ completion latencies
+// One wave per workgroup: cycles from issuing (mode 0) a 16-byte-per-lane store to rows 4 KiB
+// apart, (mode 1) a global->LDS copy of the same shape, (mode 2) the store followed by the
+// copy, until s_waitcnt vmcnt(0) returns.  vmcnt retires in issue order, so mode 2 shows how
+// long a copy issued behind a store is held back by that store's acknowledgement.  Averaged
+// over `iters` rounds, each on fresh addresses; reported in shader cycles.
+__global__ __launch_bounds__(64) void latency_kernel(char* __restrict__ buf, size_t span, int iters,
+                                                     int mode, float* out, Clk* clk) {
+  extern __shared__ __align__(16) char smc[];
+  const int lane = threadIdx.x;
+  const uint32_t lds = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)smc);
+  uint64_t total = 0;
+  const uint64_t r0 = real_clock(), c00 = shader_clock();
+  for (int it = 0; it < iters; ++it) {
+    const size_t blk = ((size_t)blockIdx.x * iters + it) * (64 * 4096) % span;
+    char* st = buf + blk + (size_t)(lane >> 1) * 4096 + (lane & 1) * 16;            // 32 rows x 32 bytes
+    const char* ld = buf + span + blk + (size_t)(lane >> 2) * 4096 + (lane & 3) * 16;  // 16 rows x 64 bytes
+    const uint4 v = make_uint4(lane, it, 2, 3);
+    wait_vm<0>();
+    const uint64_t c0 = shader_clock();
+    if (mode != 1) *reinterpret_cast<uint4*>(st) = v;
+    if (mode != 0) dma16(ld, lds);
+    wait_vm<0>();
+    total += shader_clock() - c0;
+  }
+  const uint64_t c1 = shader_clock(), r1 = real_clock();
+  if (lane == 0) out[blockIdx.x] = (float)total / iters;
+  if (blockIdx.x == 0 && lane == 0) *clk = Clk{c1 - c00, r1 - r0};
+}
+
 // ------------------------------------------------------------------ HBM streaming copy
 __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src,
                                                    uint4* __restrict__ dst, size_t n) {
@@ -459,6 +490,21 @@ extern "C" int moe_prism_microbench(int32_t max_results, moe_prism_microbench_re
     ok = run_stream<8, 4, false>(b, ncu, fps[f], 1, &v, &mhz);
     __builtin_snprintf(nm, sizeof(nm), "global_to_regs_dwordx4_row_per_lane_4waves_%s", fpn[f]);
     put(nm, v, "TB/s", mhz);
+  }
+  // 4b. completion latency of a store, a copy, and a copy behind a store: one wave alone on the
+  // chip, and one wave on every CU at once
+  for (int load = 0; load < 2 && ok; ++load) {
+    const char* mname[3] = {"store_16B_rows_ack", "global_to_lds_copy", "copy_issued_behind_store"};
+    for (int mode = 0; mode < 3 && ok; ++mode) {
+      const int grid = load ? ncu : 1, iters = 2000;
+      ok = timed(b, 1, [&] { latency_kernel<<<grid, 64, 1024>>>(b.big, (size_t)1 << 30, iters, mode, b.out, b.clk); }, &ms, &mhz);
+      std::vector<float> h(grid);
+      (void)hipMemcpy(h.data(), b.out, grid * sizeof(float), hipMemcpyDeviceToHost);
+      double sum = 0;
+      for (float f : h) sum += f;
+      __builtin_snprintf(nm, sizeof(nm), "latency_%s_%s", mname[mode], load ? "all_cus" : "one_wave");
+      put(nm, sum / grid, "cycles", mhz);
+    }
   }
   // 5. HBM streaming copy, 1 GiB
   if (ok) {
