@@ -2,11 +2,23 @@
 """Benchmark of the routed-expert forward (route -> dispatch -> grouped FFN -> combine).
 
 One "step" is one call of moe_prism_layer over one batch of synthetic tokens that is
-already resident in HBM.  Prints ONE JSON line: whole-layer routed tokens/s, the
-roofline of the dominant kernel (gate-up GEMM) from HIP events recorded around it inside the
-timed region, the other kernels' times from up to 10 further steps with events around every
-kernel (outside the timed region, so that the throughput figure carries two event records per
-step instead of eighteen), and the CPU oracle timed on a bounded sample of the same workload.
+already resident in HBM.  Prints ONE JSON line:
+
+  * value / ms_per_step: whole-layer routed tokens/s over exactly --steps back-to-back steps
+    (wall clock between two device synchronisations); in that region only the dominant
+    kernel (the grouped FFN) is bracketed by HIP events, recorded on the launch stream, which
+    give the `roofline` object;
+  * a second, untimed pass of max(--steps, 50) steps with events around every kernel and
+    around the whole step gives per-stage medians with p10/p90 (`layer_ms`, `kernels_ms`,
+    `kernels_ms_p10`, `kernels_ms_p90`), achieved GB/s and % of HBM peak per stage;
+  * ragged-group figures of the batch (`groups`): largest group, m-tiles, rows-per-tile
+    histogram, padding of the 256-row tiles and of the 32-row blocks the matrix cores run;
+  * the FFN's utilisation against the datasheet peak and against the ceilings measured on this
+    chip (profiles/microbench_mi355x.txt: matrix cores with random data, from registers / LDS);
+  * the CPU oracle timed on a bounded sample of the same workload.
+
+`roofline.traffic` (HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE /
+WRITE_SIZE runs) is read from profiles/hbm_traffic.txt, the summary of those runs.
 """
 import argparse
 import json
@@ -21,11 +33,47 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured for that workload.
-TRAFFIC_BYTES = {"c3_fine_128x4": 2.27e9,   # gate-up kernel: 2.143 GB fetched + 0.122 GB written
-                 "c2_mixtral_8x4": 4.51e9,  # 4.361 + 0.152 (weights of a group reach several XCDs' L2)
-                 "c4_decode_64x2": 1.70e9}  # 1.608 + 0.093
+
+def read_table(name):
+    """Whitespace-separated rows of a summary under profiles/ ('#' starts a comment)."""
+    rows = []
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return rows
+    for line in open(path):
+        line = line.split("#", 1)[0].strip()
+        if line:
+            rows.append(line.split())
+    return rows
+
+
+def traffic_bytes(workload, kernel):
+    """HBM bytes per launch (fetch + write) of `kernel` on `workload`, or None if not measured."""
+    for r in read_table("hbm_traffic.txt"):
+        if len(r) >= 4 and r[0] == workload and r[1] == kernel:
+            return float(r[2]) + float(r[3])
+    return None
+
+
+def measured_peaks():
+    """Matrix-core ceilings measured by `bench.py --microbench` (TFLOP/s), or {}."""
+    peaks = {}
+    for r in read_table("microbench_mi355x.txt"):
+        if len(r) >= 3 and r[2] == "TFLOP/s":
+            peaks[r[0]] = float(r[1])
+    out = {}
+    lds = [v for k, v in peaks.items() if k.startswith("mfma_lds_fed") and k.endswith("_random")]
+    reg = [v for k, v in peaks.items() if "registers_random" in k]
+    if lds:
+        out["lds_fed_random_data"] = max(lds)
+    if reg:
+        out["registers_random_data"] = max(reg)
+    return out
+
+
+def pct(v, q):
+    import numpy as np
+    return float(np.percentile(np.asarray(v, dtype=np.float64), q)) if len(v) else 0.0
 
 
 def main():
@@ -34,7 +82,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3_fine_128x4",
-                    help="c2_mixtral_8x4 | c3_fine_128x4 | c4_decode_64x2 | c5a_s1_k8 | c5b_s4_k32")
+                    help="c2_mixtral_8x4 | c3_fine_128x4 | c4_decode_64x2 | c5a_s1_k8 | c5b_s4_k32 | "
+                         "c3_paper_k (the c3 layer with the paper's budget generator, Sec. 4.2 Eq. 7)")
     ap.add_argument("--tokens", type=int, default=None, help="token count for the c5 sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
@@ -72,11 +121,10 @@ def main():
                                          for n, v, u, m in rows]}))
         return
     if args.route == "proxy":
-        from paper_2510_19366_amd.compare_modes import request_budgets
         whole = W.config("c5a_s1_k8", T=args.tokens)
         wl = W.split_workload(whole, 4)
         wl.name, wl.routed_scale = "c5b_s4_proxy_gate", 1.0
-        wl.req_k, wl.k_tok = request_budgets(wl.T, 64, 8, 32, seed=3)
+        wl.req_k, wl.k_tok = W.request_budgets(wl.T, 64, 8, 32, seed=3)
         pg = W.make_proxy_gate(whole, wl, m=8, r=4, seed=6)
         del whole
     else:
@@ -108,9 +156,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: HIP events around the dominant kernel only (the roofline figure); the other
-    # kernels' durations come from a short pass of their own afterwards, outside the timing
-    dom = "ffn_fused" if B.ffn_path(shape) == "fused" else "ffn_gate_up"
+    # ---- timed region: HIP events around the dominant kernel only (the roofline figure)
+    fused = B.ffn_path(shape) == "fused"
+    dom = "ffn_fused" if fused else "ffn_gate_up"
     B.moe_prism_timing_select([dom])
     B.moe_prism_timing_enable(True)
     B.moe_prism_timing_read()
@@ -120,42 +168,72 @@ def main():
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kt = B.moe_prism_timing_read()
-    B.moe_prism_timing_select(None)
-    for _ in range(min(args.steps, 10)):
-        step()
-    torch.cuda.synchronize()
-    kt_all = B.moe_prism_timing_read()
-    B.moe_prism_timing_enable(False)
-    kt = {k: (kt[k] if k == dom else v) for k, v in kt_all.items()}
+    kt_dom = B.moe_prism_timing_read()[dom]
     flags, pairs = B.moe_prism_status(ws)
     assert flags == 0 and pairs == wl.pairs, (flags, pairs, wl.pairs)
 
+    # ---- distribution pass (untimed): events around every kernel and around the step
+    B.moe_prism_timing_select(None)
+    n_dist = max(args.steps, 50)
+    per_kernel = {k: [] for k in B.KERNEL_NAMES}
+    layer_samples = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(n_dist):
+        e0.record()
+        step()
+        e1.record()
+        e1.synchronize()
+        layer_samples.append(e0.elapsed_time(e1))
+        for k, (ms, calls) in B.moe_prism_timing_read().items():
+            per_kernel[k].append(ms)          # per-step sum (the proxy gate launches some kernels twice)
+    B.moe_prism_timing_enable(False)
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = wl.T / (ms_per_step * 1e-3)
-    # average launch duration; with the proxy gate the route stage launches the logits, top-k,
-    # dispatch, tile and gate-up kernels a second time on small shapes, so there the figures
-    # are per-step sums
-    if args.route == "proxy":
-        kern_ms = {k: v[0] / (args.steps if k == dom else min(args.steps, 10))
-                   for k, v in kt.items()}
-    else:
-        kern_ms = {k: (v[0] / max(v[1], 1)) for k, v in kt.items()}
+    # launches of the dominant kernel per step: 1, or 2 with the proxy gate on the two-kernel path
+    dom_ms = kt_dom[0] / max(kt_dom[1], 1)    # average launch duration inside the timed region
+    kern_med = {k: pct(v, 50) for k, v in per_kernel.items()}
     P, d, Is, E = wl.pairs, wl.d, wl.inter_sub, wl.E
 
-    # dominant kernel: the gate-up GEMM (2/3 of the FFN FLOPs); algorithmic FLOPs = 4*d*Is per pair
+    # dominant kernel: the fused FFN (6*d*Is FLOP per pair) or, on the two-kernel path, the
+    # gate-up GEMM (4*d*Is per pair, 2/3 of the FFN)
     ffn_flops = 6.0 * d * Is * P
-    gu_flops = ffn_flops if dom == "ffn_fused" else 4.0 * d * Is * P
-    gu_tflops = gu_flops / (kern_ms[dom] * 1e-3) / 1e12
-    ffn_ms = kern_ms["ffn_gate_up"] + kern_ms["ffn_down"] + kern_ms["ffn_tiles"] + kern_ms["ffn_fused"]
+    dom_flops = ffn_flops if fused else 4.0 * d * Is * P
+    dom_tflops = dom_flops / (dom_ms * 1e-3) / 1e12
+    ffn_ms = sum(kern_med[k] for k in ("ffn_tiles", "ffn_gate_up", "ffn_down", "ffn_fused"))
     ffn_tflops = ffn_flops / (ffn_ms * 1e-3) / 1e12
     el = 2 if wl.dtype == "bf16" else 4
+    # algorithmic bytes per stage
     stage_bytes = {
         "logits": wl.T * d * el + E * d * el + wl.T * E * 4,
         "topk": wl.T * E * 4 + 2 * wl.T * wl.k_max * 4,
+        "dispatch_count": wl.T * wl.k_max * 4,
+        "dispatch_place": 3 * wl.T * wl.k_max * 4,
         "combine": P * d * el + wl.T * d * el + 2 * P * 4,
+        "ffn_gate_up": P * d * el + 2 * E * d * Is * el + P * Is * el,
         "ffn_down": P * Is * el + E * d * Is * el + P * d * el,
+        "ffn_fused": P * d * el + 3 * E * d * Is * el + P * d * el,
     }
+    stage_gbs = {k: v / (kern_med[k] * 1e-3) / 1e9 for k, v in stage_bytes.items() if kern_med.get(k, 0) > 0}
+
+    # ragged groups of this batch, from the dispatch tables the layer left in the workspace
+    cnt = B.layer_intermediates(shape, ws)["group_count"].cpu().numpy().astype(np.int64)
+    tiles = []
+    for n in cnt[cnt > 0]:
+        tiles += [256] * int(n // 256) + ([int(n % 256)] if n % 256 else [])
+    tiles = np.asarray(tiles, dtype=np.int64)
+    hist_edges = [(1, 32), (33, 64), (65, 128), (129, 255), (256, 256)]
+    groups = {
+        "non_empty": int((cnt > 0).sum()), "of": int(E), "max_group": int(cnt.max()) if cnt.size else 0,
+        "median_group": float(np.median(cnt)) if cnt.size else 0.0,
+        "m_tiles": int(tiles.size),
+        "rows_per_tile_hist": {f"{a}-{b}" if a != b else str(a): int(((tiles >= a) & (tiles <= b)).sum())
+                               for a, b in hist_edges},
+        "pad_waste_pct_256_row_tiles": 100.0 * (1.0 - P / max(256.0 * tiles.size, 1.0)),
+        "pad_waste_pct_32_row_blocks": 100.0 * (1.0 - P / max(float((-(-tiles // 32) * 32).sum()), 1.0)),
+    }
+
+    peaks = measured_peaks()
     res = {
         "metric": "routed tokens/sec (whole layer, mixed per-request k, 1 GPU); grouped-FFN MFMA util in ffn_mfma_util_pct",
         "value": tokens_per_s,
@@ -171,17 +249,25 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "T": wl.T, "d": d, "n_experts": wl.n_experts,
                    "n_sub": wl.n_sub, "inter_sub": Is, "k_max": wl.k_max, "pairs": P,
-                   "requests": int(len(wl.req_k)), "k_mix": "per-request", "route": args.route},
+                   "requests": int(len(wl.req_k)), "k_mix": "per-request", "route": args.route,
+                   "ffn_path": "fused" if fused else "split"},
         "ffn_mfma_util_pct": 100.0 * ffn_tflops / PEAK_BF16_TFLOPS,
+        "ffn_mfma_util_pct_measured": {k: 100.0 * ffn_tflops / v for k, v in peaks.items()},
         "ffn_tflops": ffn_tflops,
         "ffn_ms": ffn_ms,
-        "roofline": {"kernel": dom, "bound": "mfma", "achieved": gu_tflops,
+        "roofline": {"kernel": dom, "bound": "mfma", "achieved": dom_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gu_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": TRAFFIC_BYTES.get(wl.name)},
-        "kernels_ms": kern_ms,
-        "stage_gbs": {k: v / (kern_ms[k] * 1e-3) / 1e9 for k, v in stage_bytes.items()
-                      if kern_ms.get(k, 0) > 0},
+                     "frac": dom_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": traffic_bytes(wl.name, dom),
+                     "avg_launch_ms": dom_ms},
+        "layer_ms": {"median": pct(layer_samples, 50), "p10": pct(layer_samples, 10),
+                     "p90": pct(layer_samples, 90), "samples": n_dist},
+        "kernels_ms": kern_med,
+        "kernels_ms_p10": {k: pct(v, 10) for k, v in per_kernel.items()},
+        "kernels_ms_p90": {k: pct(v, 90) for k, v in per_kernel.items()},
+        "stage_gbs": stage_gbs,
+        "stage_pct_hbm": {k: 100.0 * v / PEAK_HBM_GBS for k, v in stage_gbs.items()},
+        "groups": groups,
     }
 
     if args.graph:

@@ -32,15 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def request_budgets(T, n_req, k_lo, k_hi, seed):
-    """Per-request budgets in sub-expert units, uniform in [k_lo, k_hi], and their per-token
-    expansion (equal-length requests)."""
-    rng = np.random.default_rng(seed)
-    req_k = rng.integers(k_lo, k_hi + 1, size=n_req).astype(np.int32)
-    per = T // n_req
-    k_tok = np.repeat(req_k, per)
-    k_tok = np.concatenate([k_tok, np.full(T - k_tok.size, req_k[-1], np.int32)]).astype(np.int32)
-    return req_k, k_tok
+from paper_2510_19366_amd.workloads import request_budgets  # noqa: E402  (re-exported for callers)
 
 
 def mode_budgets(k_sub, S, mode):

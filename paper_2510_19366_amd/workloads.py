@@ -54,6 +54,17 @@ def expand_requests(req_k: np.ndarray, req_off: np.ndarray) -> np.ndarray:
     return k_tok
 
 
+def request_budgets(T, n_req, k_lo, k_hi, seed):
+    """Per-request budgets in sub-expert units, uniform in [k_lo, k_hi], and their per-token
+    expansion (equal-length requests)."""
+    rng = np.random.default_rng(seed)
+    req_k = rng.integers(k_lo, k_hi + 1, size=n_req).astype(np.int32)
+    per = T // n_req
+    k_tok = np.repeat(req_k, per)
+    k_tok = np.concatenate([k_tok, np.full(T - k_tok.size, req_k[-1], np.int32)]).astype(np.int32)
+    return req_k, k_tok
+
+
 def paper_k_targets(rng: np.random.Generator, n: int, mu: float, sigma: float,
                     k_max: int) -> np.ndarray:
     """Budget generator of Sec. 4.2, Eq. 7: clip(round(N(mu, sigma^2)), 1, k_max)."""
@@ -164,7 +175,7 @@ def make_workload(name: str, *, dtype: str, d: int, n_experts: int, n_sub: int,
 
 
 CONFIG_NAMES = ("c1_tiny_f32", "c2_mixtral_8x4", "c3_fine_128x4", "c4_decode_64x2",
-                "c5a_s1_k8", "c5b_s4_k32")
+                "c5a_s1_k8", "c5b_s4_k32", "c3_paper_k")
 
 
 def config(name: str, *, T: Optional[int] = None, with_weights: bool = True,
@@ -182,6 +193,13 @@ def config(name: str, *, T: Optional[int] = None, with_weights: bool = True,
     if name == "c3_fine_128x4":
         return make_workload(name, dtype="bf16", d=2048, n_experts=128, n_sub=4, inter_sub=192,
                              req_tokens=(64, 256 // scale_down), k_lo=8, k_hi=32, k_max=32,
+                             seed=3, bias_std=1.0, with_weights=with_weights)
+    if name == "c3_paper_k":
+        # the c3 layer with the paper's own budget generator (Sec. 4.2, Eq. 7): one budget per
+        # request, clip(round(N(16, 5^2)), 1, 32); an extra workload, not one of the five configs
+        req_k = paper_k_targets(np.random.default_rng(33), 64, 16.0, 5.0, 32)
+        return make_workload(name, dtype="bf16", d=2048, n_experts=128, n_sub=4, inter_sub=192,
+                             req_tokens=(64, 256 // scale_down), req_k=req_k, k_max=32,
                              seed=3, bias_std=1.0, with_weights=with_weights)
     if name == "c4_decode_64x2":
         return make_workload(name, dtype="bf16", d=2048, n_experts=64, n_sub=2, inter_sub=704,

@@ -82,7 +82,7 @@ def test_proxy_gate_full_size_sampled():
     # Sec. 3.2.2 training-free proxy gate at the benchmark's size (bench.py --route proxy):
     # 128 experts split in 4, m = 8, r = 4, per-request budgets in [8, 32]; routing checked with
     # the margin rule and outputs against the oracle on a random sample of tokens
-    from paper_2510_19366_amd.compare_modes import request_budgets
+    from paper_2510_19366_amd.workloads import request_budgets
     from test_gpu_proxy import OUT_TOL, check_route
     whole = W.config("c5a_s1_k8", T=16384)
     split = W.split_workload(whole, 4)
