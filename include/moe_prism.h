@@ -55,6 +55,8 @@ extern "C" {
 
 /* status-word bits (moe_prism_status) */
 #define MOE_PRISM_STATUS_K_CLAMPED 1 /* some k_tok[t] was outside [0, k_max] and was clamped */
+#define MOE_PRISM_STATUS_TILES_TRUNCATED 2 /* group offsets describe more 256-row tiles than the
+                                              workspace's tile table holds: rows were left out */
 
 /*
  * Problem shape (host struct, read during the call, not retained).
@@ -188,7 +190,8 @@ MOE_PRISM_API int moe_prism_layer_static(const moe_prism_shape* shape, const voi
  *             0 <= kappa_j <= S, sum k.  Entries outside [0, S] are clamped.
  *   k_tok     [T] budgets in sub-expert units, 0 <= k_t <= min(k_max, m*S); others are clamped
  *             and flagged in the status word.
- * Requirements beyond moe_prism_shape's: m <= N, S <= 16, m*rows_half <= k_max*inter_sub
+ * Requirements beyond moe_prism_shape's: m <= N, S <= 16, m*rows_half <= k_max*inter_sub,
+ * T*m/256 + N <= T*k_max/256 + E (the stage shares the layer's tile table)
  * (MOE_PRISM_ERR_UNSUPPORTED_SHAPE otherwise).  Scores are taken from activations in the
  * activation dtype (bf16: rounded once) and summed in fp32.  Uses the logits, tile and
  * intermediate-activation regions of ws and the start of its y region as scratch: do not call

@@ -215,6 +215,10 @@ static int check_proxy(const moe_prism_shape* s, int m, int r, int rows_half) {
     return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
   // the stage's activations [T*m, rows_half] live in the h region, its tables in the y region
   if ((long)m * rows_half > (long)s->k_max * s->inter_sub) return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  // the stage's T*m pairs over N groups are cut into m-tiles in the layer's tile table
+  // (T*k_max / FFN_BM + E entries): they must fit (always true for m <= k_max)
+  const long table = (long)s->T * s->k_max / FFN_BM + (long)s->n_experts * s->n_sub;
+  if ((long)s->T * m / FFN_BM + s->n_experts > table) return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
   if (4L * align256((size_t)s->T * m * 4) + 2L * align256(((size_t)s->n_experts + 1) * 4) >
       (long)s->T * s->k_max * s->d * el)
     return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;

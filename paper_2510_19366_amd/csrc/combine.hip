@@ -57,8 +57,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
   kt = kt < 0 ? 0 : (kt > k_max ? k_max : kt);
   for (int j = threadIdx.x; j < kt; j += 256) {
     const int sl = slot_of_pair[(size_t)t * k_max + j];
-    const bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing
-    s_slot[j] = ok ? sl : 0;
+    const bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing:
+    s_slot[j] = ok ? sl : -1;                // its row is not even read (y may hold anything there)
     s_w[j] = ok ? w[(size_t)t * k_max + j] : 0.0f;
   }
   __syncthreads();
@@ -68,7 +68,15 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
     for (; j + RU <= kt; j += RU) {  // RU rows in flight, still added in ascending j
       float v[RU][8];
 #pragma unroll
-      for (int u = 0; u < RU; ++u) Vec<DT>::load(y, (size_t)s_slot[j + u] * d + col, v[u]);
+      for (int u = 0; u < RU; ++u) {
+        const int sl = s_slot[j + u];  // the same for every thread: a uniform branch
+        if (sl >= 0) {
+          Vec<DT>::load(y, (size_t)sl * d + col, v[u]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[u][e] = 0.0f;
+        }
+      }
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
         const float wj = s_w[j + u];
@@ -77,9 +85,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
       }
     }
     for (; j < kt; ++j) {
-      float v[8];
+      float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
       const float wj = s_w[j];
-      Vec<DT>::load(y, (size_t)s_slot[j] * d + col, v);
+      const int sl = s_slot[j];
+      if (sl >= 0) Vec<DT>::load(y, (size_t)sl * d + col, v);
 #pragma unroll
       for (int e = 0; e < N; ++e) acc[e] = fmaf(wj, v[e], acc[e]);
     }

@@ -3,18 +3,20 @@
 //   down    : y[p, q] = sum_c h[p,c] * Wd[g,q,c]
 // over ragged groups, as persistent workgroups that walk (m-tile, n-tile) items.
 //
-// Tile: 256 slot rows x BN weight rows (BN = 256 or 192), K slabs of 64, 8
-// wavefronts (4 along the slot rows x 2 along the weight rows), one workgroup
-// per CU.  Per K step of 16 a wave multiplies 2 slot blocks by BN/64 weight
-// blocks of 32 rows with v_mfma_f32_32x32x16_bf16 (measured at twice the rate
-// of the 16x16x32 form on this chip).  The weight block is the MFMA's first
-// operand and its rows are fed in a permuted order, so that a lane ends up
-// with 8 or 16 consecutive output columns of one slot row and stores them as
-// 16-byte words.  Operand slabs go global -> registers ->
-// LDS (XOR-swizzled, conflict-free for the fragment reads) one slab ahead of
-// the MFMAs, and the software pipeline runs across item boundaries: the first
-// slab of the next item is fetched while the last slab of the current one is
-// multiplied and its outputs are stored.
+// Tile: 256 slot rows x BN weight rows (BN = 256 or 192), 8 wavefronts (4 along the slot
+// rows x 2 along the weight rows), one workgroup per CU.  Per K step of 16 a wave multiplies
+// 2 slot blocks by BN/64 weight blocks of 32 rows with v_mfma_f32_32x32x16_bf16 (measured at
+// twice the rate of the 16x16x32 form on this chip).  The weight block is the MFMA's first
+// operand and its rows are fed in a permuted order, so that a lane ends up with 8 or 16
+// consecutive output columns of one slot row and stores them as 16-byte words.
+// Main driver (run_items_dma): operand slabs go global -> LDS directly
+// (global_load_lds_dwordx4) through a ring of 4-5 stages of 32 K-elements that runs across
+// item boundaries, with explicit s_waitcnt vmcnt counts and one s_barrier per stage; for
+// long K the two wave groups alternate between multiplying and preparing the next stage.
+// Fallback (run_items, K too short for the ring): 64-wide slabs through registers into a
+// double-buffered, XOR-swizzled LDS tile, one slab ahead of the MFMAs.
+// Narrow sub-experts (Is in {64, 128, 192}) take the fused kernel in ffn_fused_bf16.hip
+// instead; these two kernels serve every other shape.
 #include "ffn_common.h"
 
 namespace mp {
@@ -474,12 +476,22 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
 }
 // one wave-wide copy: every lane fetches 16 (4) bytes at g; lane i's data lands at lds + 16 i (4 i)
+// m0 carries the LDS address of the copy.  The compiler reserves m0 and does not accept it in
+// a clobber list, so the value it may be keeping there is saved and put back.
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds)
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 1\n\tglobal_load_lds_dwordx4 %1, off\n\t"
+               "s_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(g), "s"(lds)
                : "memory");
 }
 __device__ __forceinline__ void dma4(const void* g, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 1\n\tglobal_load_lds_dword %0, off" ::"v"(g), "s"(lds)
+  uint32_t keep;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 1\n\tglobal_load_lds_dword %1, off\n\t"
+               "s_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(g), "s"(lds)
                : "memory");
 }
 template <int N>

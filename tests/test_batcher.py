@@ -7,10 +7,18 @@ import pytest
 from oracle import batcher_oracle as BO
 from paper_2510_19366_amd import binding as B
 
-N_GRID, K_GRID = [256, 1024, 4096, 16384], [8, 16, 24, 32]
-# T(n, k) of the fine layout measured on MI355X (ms per layer)
-MEASURED = [[0.365, 0.363, 0.366, 0.375], [0.369, 0.389, 0.408, 0.429],
-            [0.488, 0.566, 0.664, 0.819], [1.006, 1.532, 2.069, 2.600]]
+# T(n, k) of the fine layout measured on MI355X (ms per layer): the tracked summary of
+# `compare_modes --table` under profiles/
+from paper_2510_19366_amd.compare_modes import read_time_table
+
+N_GRID, K_GRID, MEASURED = read_time_table()
+
+
+def test_measured_table_is_a_time_table():
+    assert N_GRID == sorted(N_GRID) and K_GRID == sorted(K_GRID) and len(MEASURED) == len(N_GRID)
+    ms = np.asarray(MEASURED)
+    assert ms.shape == (len(N_GRID), len(K_GRID)) and (ms > 0).all()
+    assert (np.diff(ms, axis=0) > 0).all()              # more tokens never cost less
 
 
 def table(fn):

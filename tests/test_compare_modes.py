@@ -49,6 +49,10 @@ def test_request_budgets_shape_and_range():
     assert set(np.unique(k_tok)) <= set(req_k.tolist())
 
 
+def test_fifo_batches_helper():
+    assert M.fifo_batches([5, 5, 5, 20, 3], 10) == [[0, 1], [2], [3], [4]]
+
+
 @pytest.mark.gpu
 def test_batch_max_changes_only_under_budget_tokens():
     import torch
@@ -75,3 +79,10 @@ def test_batch_max_changes_only_under_budget_tokens():
     assert at_max.any() and (~at_max).any()
     assert np.array_equal(own[at_max].view(np.uint32), bmax[at_max].view(np.uint32))
     assert np.all(np.any(own[~at_max] != bmax[~at_max], axis=1))
+    # each mode against the oracle run with that mode's budgets
+    from oracle import oracle as O
+    from gpu_util import max_rel
+    for k_mode, got in ((k_sub, own), (k_bmax, bmax)):
+        ref = O.layer(f.x, f.w_router, f.router_bias, k_mode.astype(np.int32), f.w_gate_up, f.w_down,
+                      f.k_max, f.renormalize, f.routed_scale)
+        assert max_rel(got, ref) <= 2e-2

@@ -1,7 +1,10 @@
 """GPU parity at the benchmark's full sizes, through moe_prism_layer (the launch
 configuration bench.py times).  Routing ids and dispatch tables are compared with the
-oracle for ALL tokens, bit for bit; layer outputs on a random sample of tokens the
-oracle evaluates one by one."""
+oracle for ALL tokens, bit for bit.  Layer outputs: against the oracle on ALL tokens for
+configs 2, 3 and 4 (tile interiors at the timed launch shape included), on 2048 random
+tokens for the uniform-k sweep at 16K tokens and above, with both error figures: the largest
+error relative to the largest reference magnitude (the layer tolerance), and the largest
+per-row error relative to that row's largest magnitude (a wrong low-magnitude row fails)."""
 import functools
 
 import numpy as np
@@ -11,9 +14,11 @@ import torch
 from oracle import oracle as O
 from paper_2510_19366_amd import binding as B
 from paper_2510_19366_amd import workloads as W
-from gpu_util import max_rel, run_layer, to_np
+from gpu_util import max_rel, row_rel, run_layer, to_np
 
 pytestmark = pytest.mark.gpu
+
+ROW_TOL = 4e-2      # largest per-row error relative to the row's largest reference magnitude
 
 
 @functools.lru_cache(maxsize=2)
@@ -36,13 +41,20 @@ def check_full(wl, n_sample, seed=0):
     cnt, off, sp, sl = O.dispatch(ids, wl.E)
     assert np.array_equal(inter["group_count"], cnt) and np.array_equal(inter["group_offset"], off)
     assert np.array_equal(inter["sorted_pair"], sp) and np.array_equal(inter["slot_of_pair"], sl)
-    # outputs: sampled tokens, one by one
-    tok = np.sort(np.random.default_rng(seed).choice(wl.T, size=n_sample, replace=False)).astype(np.int32)
+    # outputs: the sampled tokens (all of them when n_sample >= T), one by one
+    if n_sample >= wl.T:
+        tok = np.arange(wl.T, dtype=np.int32)
+    else:
+        tok = np.sort(np.random.default_rng(seed).choice(wl.T, size=n_sample, replace=False)).astype(np.int32)
     ref, _, _ = O.layer_tokens(tok, wl.x, wl.w_router, wl.router_bias, wl.k_tok, wl.w_gate_up,
                                wl.w_down, wl.k_max, wl.renormalize, wl.routed_scale)
     got = to_np(out)
     err = max_rel(got[tok], ref)
     assert err <= 2e-2, err
+    # per row: two bf16 roundings (h, y) of up to k_max summed rows plus the output rounding stay
+    # within a few 2^-8 of the row's largest element; a dropped or misplaced pair is ~1/k_t of it
+    rerr = row_rel(got[tok], ref)
+    assert rerr <= ROW_TOL, rerr
     assert np.isfinite(got).all()
     assert np.all(got[wl.k_tok == 0] == 0)
     return got, cnt
@@ -51,20 +63,20 @@ def check_full(wl, n_sample, seed=0):
 def test_c3_fine_128x4_full():
     wl = workload("c3_fine_128x4")
     assert (wl.T, wl.E, wl.inter_sub, wl.k_max) == (16384, 512, 192, 32)
-    _, cnt = check_full(wl, n_sample=96)
+    _, cnt = check_full(wl, n_sample=wl.T)
     assert cnt.max() > 8 * max(1, int(np.median(cnt)))       # the bias makes the load skewed
 
 
 def test_c4_decode_64x2_full():
     wl = workload("c4_decode_64x2")
     assert (wl.T, wl.E, wl.inter_sub) == (8192, 128, 704) and set(np.unique(wl.k_tok)) == {4, 12}
-    check_full(wl, n_sample=96)
+    check_full(wl, n_sample=wl.T)
 
 
 def test_c2_mixtral_8x4_full():
     wl = workload("c2_mixtral_8x4")
     assert (wl.T, wl.d, wl.E, wl.inter_sub) == (4096, 4096, 32, 3584)
-    check_full(wl, n_sample=24)
+    check_full(wl, n_sample=wl.T)
 
 
 @pytest.mark.parametrize("T", [512, 2048, 16384, 65536])
@@ -73,8 +85,9 @@ def test_c5_matched_budget_split_vs_whole(T):
     a = W.config("c5a_s1_k8", T=T)
     b = W.split_workload(a, 4)
     assert (b.E, b.k_max, b.inter_sub, b.routed_scale) == (512, 32, 192, 4.0)
-    got_a, _ = check_full(a, n_sample=32, seed=1)
-    got_b, _ = check_full(b, n_sample=32, seed=1)
+    n = 2048 if T >= 16384 else T
+    got_a, _ = check_full(a, n_sample=n, seed=1)
+    got_b, _ = check_full(b, n_sample=n, seed=1)
     assert max_rel(got_b, got_a) <= 2e-2
 
 
@@ -106,8 +119,10 @@ def test_proxy_gate_full_size_sampled():
     same, ref = check_route(sub, pg, k_tok[tok], ids[tok], w[tok], "bf16")
     assert same.mean() >= 0.9
     got = to_np(out)[tok]
-    for i in np.nonzero(same)[0]:
-        want = sum(ref["w"][i, j] * O.ffn_one(sub.x[i], split.w_gate_up[ref["ids"][i, j]],
-                                              split.w_down[ref["ids"][i, j]])
+    for i in range(len(tok)):
+        # identical routing: the oracle's ids; a choice inside the tie set (validated by
+        # check_route): the oracle FFN on the DEVICE's ids with the inherited weights
+        use_ids, use_w = (ref["ids"][i], ref["w"][i]) if same[i] else (ids[tok[i]], w[tok[i]])
+        want = sum(use_w[j] * O.ffn_one(sub.x[i], split.w_gate_up[use_ids[j]], split.w_down[use_ids[j]])
                    for j in range(k_tok[tok[i]]))
-        assert max_rel(got[i], want) <= OUT_TOL["bf16"]
+        assert max_rel(got[i], want) <= OUT_TOL["bf16"], (i, same[i])

@@ -269,3 +269,32 @@ def test_other_tokens_budgets_do_not_matter():
     b = to_np(out2)
     same = wl.k_tok == k2
     assert np.array_equal(a[same], b[same]) and not np.array_equal(a[~same], b[~same])
+
+
+def test_combine_never_reads_the_row_of_a_pick_without_a_slot():
+    # standalone combine: a pick whose slot is -1 contributes nothing, whatever y holds (here
+    # NaN in every row, so that reading any row for it, even times zero, would show)
+    T, d, k_max = 5, 128, 3
+    shape = B.make_shape(T, d, 4, 2, 32, k_max, "bf16")
+    rng = np.random.default_rng(2)
+    y = torch.from_numpy(rng.standard_normal((T * k_max, d)).astype(np.float32)).cuda().bfloat16()
+    slot = rng.permutation(T * k_max).astype(np.int32).reshape(T, k_max)
+    slot[1, 0] = -1
+    slot[3, 2] = -1
+    y[0] = float("nan")                      # row 0 is where a redirected pick would have read
+    used0 = np.argwhere(slot == 0)
+    slot[used0[:, 0], used0[:, 1]] = -1     # nobody legitimately reads row 0
+    w = rng.random((T, k_max)).astype(np.float32)
+    k_tok = np.full(T, k_max, np.int32)
+    out = B.moe_prism_combine(shape, y, torch.from_numpy(slot.reshape(-1)).cuda(),
+                              torch.from_numpy(w).cuda(), torch.from_numpy(k_tok).cuda())
+    torch.cuda.synchronize()
+    got = to_np(out)
+    assert np.isfinite(got).all()
+    yf = to_np(y).astype(np.float64)
+    ref = np.zeros((T, d))
+    for t in range(T):
+        for j in range(k_max):
+            if slot[t, j] >= 0:
+                ref[t] += float(w[t, j]) * yf[slot[t, j]]
+    assert max_rel(got, ref) <= 2e-2

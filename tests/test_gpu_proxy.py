@@ -97,6 +97,16 @@ def test_proxy_route_and_layer_against_oracle(dtype, case):
     got = to_np(out)
     assert max_rel(got[same], ref_out[same]) <= OUT_TOL[dtype]
     assert np.all(got[k_tok == 0] == 0)
+    # tokens whose choice differs from the oracle's inside the tie set (check_route validated
+    # it): the same stages of the oracle on the DEVICE's ids and inherited weights
+    if not same.all():
+        ids_d, w_d = to_np(ids), to_np(w)
+        cnt_d, off_d, sp_d, sl_d = O.dispatch(ids_d, split.E)
+        y_d = O.grouped_ffn(split.x, split.w_gate_up, split.w_down, off_d, sp_d, split.k_max)
+        out_d = O.combine(y_d, sl_d, w_d.astype(np.float64), np.clip(k_tok, 0, split.k_max).astype(np.int32),
+                          split.T)
+        assert max_rel(got[~same], out_d[~same]) <= OUT_TOL[dtype]
+        assert np.array_equal(inter["group_offset"], off_d) and np.array_equal(inter["sorted_pair"], sp_d)
     if same.all():                                   # identical routing: tables are comparable too
         assert np.array_equal(inter["group_offset"], off) and np.array_equal(inter["sorted_pair"], sp)
 

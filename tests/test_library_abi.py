@@ -47,3 +47,23 @@ def test_host_side_validation():
     assert m.value > n.value
     offs = B.moe_prism_layer_offsets(ok)
     assert all(v % 256 == 0 for v in offs.values()) and max(offs.values()) < n.value
+
+
+def test_proxy_stage_that_would_overflow_the_tile_table_is_refused():
+    # the proxy-gate stage cuts T*m pairs over N groups into the layer's tile table of
+    # T*k_max/256 + E entries; a shape where they do not fit is refused on the host
+    # (k_max = 2, m = 8: 2048 tiles needed, 1024 + 64 available)
+    lib = B.lib()
+    s = B.make_shape(65536, 256, 16, 4, 128, 2, "bf16")
+    n = C.c_size_t(0)
+    assert lib.moe_prism_workspace_bytes(C.byref(s), C.byref(n)) == 0
+    dummy = (C.c_char * 256)()
+    p = C.cast(dummy, C.c_void_p)
+    rc = lib.moe_prism_route_proxy(C.byref(s), p, p, None, p, C.c_int32(8), C.c_int32(1),
+                                   C.c_int32(32), p, p, p, p, p, C.c_size_t(n.value), None)
+    assert rc == -2
+    ok = B.make_shape(65536, 256, 16, 4, 128, 8, "bf16")          # m <= k_max always fits
+    assert lib.moe_prism_workspace_bytes(C.byref(ok), C.byref(n)) == 0
+    rc = lib.moe_prism_route_proxy(C.byref(ok), None, None, None, None, C.c_int32(8), C.c_int32(1),
+                                   C.c_int32(32), None, None, None, None, None, C.c_size_t(0), None)
+    assert rc == -1                                                 # passes the shape check, then null pointers
