@@ -72,8 +72,8 @@ typedef struct {
   int32_t k_max;       /* largest budget a token may carry, in sub-expert units          */
   int32_t dtype;       /* MOE_PRISM_F32 or MOE_PRISM_BF16                                */
   int32_t renormalize; /* 1: softmax over the k_t selected; 0: softmax over all E        */
-  float routed_scale;  /* multiplies every routing weight (S x the model's own factor,   */
-                       /* the "N-adjusted routed scaling" of Sec. 3.2.2)                 */
+  float routed_scale;  /* multiplies every routing weight: S x the model's own factor    */
+                       /* (the scaling by the split count that Sec. 3.2.2 prescribes)    */
 } moe_prism_shape;
 
 /* Bytes of workspace any entry point below needs for `shape` (host only). */

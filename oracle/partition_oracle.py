@@ -19,7 +19,10 @@ Readings where the text is silent: the proposal stream is a counter-based genera
 (splitmix64 of seed + 3*step + {0, 1, 2}) so that both implementations draw the same swaps:
 neuron i = r0 mod C, neuron j = r1 mod C, a proposal with both in one group is skipped (it
 still consumes its step); the acceptance draw is u = (r2 >> 11) * 2^-53; all sums are
-binary64 in ascending index order; the group sums L are updated incrementally per kept swap.
+binary64.  The reference recomputes Eq. 4 from scratch for every proposal; the library keeps
+the group sums L and updates them per kept swap, so the two agree exactly only where every
+sum is exact in binary64 (the exact-equality test uses dyadic activations for that reason) and
+to rounding elsewhere.
 """
 from __future__ import annotations
 
@@ -88,40 +91,27 @@ def greedy(A, S):
 
 
 def anneal(A, group_of, S, k_in, steps, t0, t1, seed):
-    """Returns (group_of, loss).  group_of is not modified in place."""
-    B, C = A.shape
+    """Returns (group_of, loss).  group_of is not modified in place.
+
+    Written as the definition: the loss of the current and of every proposed partition is Eq. 4
+    evaluated from scratch (objective()); nothing is carried from one step to the next but the
+    partition itself."""
+    C = A.shape[1]
     g = np.array(group_of, np.int32)
-    absA = np.abs(A.astype(np.float64))
-    L = group_mass(A, g, S)
-    k_drop = S - k_in
-    per_tok = [drop_sum(L[b].tolist(), k_drop) for b in range(B)]
-    loss = 0.0
-    for v in per_tok:
-        loss += v
+    loss = objective(A, g, S, k_in)
     for step in range(steps):
         r0 = splitmix64((seed + 3 * step) & MASK)
         r1 = splitmix64((seed + 3 * step + 1) & MASK)
         r2 = splitmix64((seed + 3 * step + 2) & MASK)
         i, j = r0 % C, r1 % C
-        gi, gj = int(g[i]), int(g[j])
-        if gi == gj:
+        if g[i] == g[j]:
             continue
         temp = t0 * (t1 / t0) ** (step / (steps - 1)) if steps > 1 else t0
-        new_tok = [0.0] * B
-        new_loss = 0.0
-        for b in range(B):
-            row = L[b].tolist()
-            row[gi] = row[gi] - absA[b, i] + absA[b, j]
-            row[gj] = row[gj] - absA[b, j] + absA[b, i]
-            new_tok[b] = drop_sum(row, k_drop)
-            new_loss += new_tok[b]
+        proposal = g.copy()
+        proposal[i], proposal[j] = g[j], g[i]
+        new_loss = objective(A, proposal, S, k_in)
         delta = new_loss - loss
         u = (r2 >> 11) * (1.0 / 9007199254740992.0)
         if delta <= 0.0 or u < math.exp(-delta / temp):
-            for b in range(B):
-                L[b, gi] = L[b, gi] - absA[b, i] + absA[b, j]
-                L[b, gj] = L[b, gj] - absA[b, j] + absA[b, i]
-            g[i], g[j] = gj, gi
-            per_tok = new_tok
-            loss = new_loss
+            g, loss = proposal, new_loss
     return g, loss

@@ -298,3 +298,61 @@ def test_combine_never_reads_the_row_of_a_pick_without_a_slot():
             if slot[t, j] >= 0:
                 ref[t] += float(w[t, j]) * yf[slot[t, j]]
     assert max_rel(got, ref) <= 2e-2
+
+
+@pytest.mark.parametrize("case", [
+    dict(dtype="bf16", T=777, d=320, N=6, S=4, Is=192, k_max=8),     # fused FFN kernel
+    dict(dtype="bf16", T=500, d=192, N=5, S=2, Is=96, k_max=5),      # two-kernel FFN
+    dict(dtype="f32", T=130, d=128, N=4, S=2, Is=64, k_max=4),
+])
+def test_guard_bands_around_workspace_y_and_out_stay_intact(case):
+    # the workspace, y (staged call: exactly P valid rows wide, the rest of its T*k_max rows must
+    # stay untouched) and out sit between 4 KiB bands of a known byte; no kernel may write outside
+    dtype = case["dtype"]
+    rng = np.random.default_rng(case["T"])
+    k = rng.integers(0, case["k_max"] + 1, size=case["T"]).astype(np.int32)
+    wl = W.make_workload("guard", dtype=dtype, d=case["d"], n_experts=case["N"], n_sub=case["S"],
+                         inter_sub=case["Is"], req_tokens=[1] * case["T"], req_k=k,
+                         k_max=case["k_max"], seed=case["T"], bias_std=1.0, w_std=0.05)
+    dev = B.to_device(wl)
+    shape = dev["shape"]
+    G, FILL = 4096, 0xA5
+    el = 2 if dtype == "bf16" else 4
+    tdt = B.act_dtype(shape)
+
+    def banded(nbytes):
+        buf = torch.full((nbytes + 2 * G + 256,), FILL, dtype=torch.uint8, device="cuda")
+        o = (-(buf.data_ptr() + G)) % 256 + G
+        return buf, buf[o:o + nbytes], o
+
+    def intact(buf, o, nbytes):
+        b = buf.cpu().numpy()
+        return bool((b[:o] == FILL).all() and (b[o + nbytes:] == FILL).all())
+
+    n_ws = B.moe_prism_workspace_bytes(shape)
+    ws_buf, ws, ws_o = banded(n_ws)
+    n_y = wl.T * wl.k_max * wl.d * el
+    y_buf, y_raw, y_o = banded(n_y)
+    n_out = wl.T * wl.d * el
+    out_buf, out_raw, out_o = banded(n_out)
+    y = y_raw.view(tdt).view(wl.T * wl.k_max, wl.d)
+    out = out_raw.view(tdt).view(wl.T, wl.d)
+
+    ids, w = B.moe_prism_route(shape, dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"], ws)
+    cnt, off, sp, sl = B.moe_prism_dispatch(shape, ids, ws)
+    B.moe_prism_grouped_ffn(shape, dev["x"], dev["w_gate_up"], dev["w_down"], off, sp, ws, y=y)
+    B.moe_prism_combine(shape, y, sl, w, dev["k_tok"], out=out)
+    torch.cuda.synchronize()
+    P = int(off[-1].item())
+    assert intact(ws_buf, ws_o, n_ws) and intact(y_buf, y_o, n_y) and intact(out_buf, out_o, n_out)
+    # rows of y beyond the P pairs are never written either
+    tail = y_raw[P * wl.d * el:].cpu().numpy()
+    assert (tail == FILL).all()
+    staged = to_np(out).copy()
+    B.moe_prism_layer(shape, dev["x"], dev["w_router"], dev["router_bias"], dev["k_tok"],
+                      dev["w_gate_up"], dev["w_down"], ws, out=out)
+    torch.cuda.synchronize()
+    assert intact(ws_buf, ws_o, n_ws) and intact(out_buf, out_o, n_out)
+    assert np.array_equal(staged, to_np(out))
+    ref = O.layer_of(wl)
+    assert max_rel(staged, ref) <= TOL[dtype]
