@@ -355,8 +355,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   //   (c) issues its copies of x(q+2) and W(q+3) (into the slots of x(q-1), W(q-1)),
   //   (d) waits until everything it issued before (c) has landed, except the output stores of
   //       the previous iteration: that is x(q+1) and its part of W(q+2) (issued in iteration
-  //       q - 1).  From here on the fragments of stage q + 1 may be read.
-  // (b)-(d) sit between MFMAs of (a) so that their scalar work and waiting hide behind them.
+  //       q - 1).  From here on the x fragments of stage q + 1 may be read.
+  // (b) and (c) sit between MFMAs of (a) so that their scalar work hides behind them; (d) closes
+  // the iteration.
   produce_w();  // W(0)
   produce_w();  // W(1)
   produce_x(nullptr);  // x(0)
@@ -383,8 +384,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   auto next_x = [&](uint32_t c) { return c + X_SLOT == NSX * X_SLOT ? 0u : c + X_SLOT; };
   constexpr int STEPS = 2 * NBLK;          // MFMAs per wave and stage, both phases
   constexpr int B_STEP = 1;                // (b), (c) after this step
-  constexpr int WT_STEP = STEPS - PD - 2;  // (d) after this step, before the first read of stage q + 1
-  constexpr int XA0_STEP = WT_STEP > NBLK - 1 ? WT_STEP : NBLK - 1;  // x fragment 0 is free and x(q+1) landed
+  // (d) after the last step: the copies get the longest possible flight (two iterations; measured
+  // 4-6 % faster than waiting earlier and reading the next stage's x fragments inside the stream);
+  // only the x fragments of stage q + 1 depend on (d), the weight fragments of stage q + 1 are
+  // already published and are read during the last PD steps
+  constexpr int WT_STEP = STEPS - 1;
   static_assert(WT_STEP > B_STEP, "order of the in-stage hooks");
 
   for (;;) {
@@ -441,7 +445,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           for (int i = 0; i < STEPS; ++i) {
             acc1[i % NBLK] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i % PD], xa[i / NBLK], acc1[i % NBLK], 0, 0, 0);
             wf[i % PD] = i + PD < STEPS ? rd_w1f(c_w, i + PD) : rd_w1f(nw, i + PD - STEPS);
-            if (i == XA0_STEP + 1) xa[0] = rd_xf(nx, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (i == B_STEP) {
               barrier();
@@ -456,6 +459,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
               __builtin_amdgcn_sched_barrier(0);
             }
           }
+          xa[0] = rd_xf(nx, 0);
           xa[1] = rd_xf(nx, 1);
           c_w = nw;
           c_x = nx;
@@ -489,11 +493,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       // instruction, and the stores alone keep the address unit busy for a quarter of the
       // kernel).  So 16 rows x 32 columns at a time go through 1 KiB of wave-private LDS and are
       // stored with 4 adjacent lanes covering 64 contiguous bytes of a row.
+      // Staging rows are 64 bytes (4 chunks of 16); chunk c of row r sits at position
+      // c ^ ((r >> 2) & 3), which makes both the 16-lane writes (16 rows, one chunk index) and the
+      // linear reads (4 rows x 4 positions) hit all 64 banks once.
       unsigned char* epi = smem + C::OFF_EPI + wv * EPI_WAVE;
-      const uint32_t epi_wr = (uint32_t)((fr & 15) * 64 + fh * 32);
-      const uint32_t epi_rd = (uint32_t)l * 16u;  // row l >> 2 of the 16, 16-byte chunk l & 3
+      const int er = fr & 15, es = (er >> 2) & 3;
+      const uint32_t epi_wr0 = (uint32_t)(er * 64 + ((2 * fh) ^ es) * 16);
+      const uint32_t epi_wr1 = (uint32_t)(er * 64 + ((2 * fh + 1) ^ es) * 16);
+      const uint32_t epi_rd = (uint32_t)l * 16u;  // row l >> 2 of the 16, position l & 3
       const int srow = wv * 32 + (l >> 2);        // + 16 for the second half of the wave's rows
-      const uint32_t vo = (uint32_t)srow * (uint32_t)d * 2u + (uint32_t)(l & 3) * 16u;
+      const int echunk = (l & 3) ^ ((l >> 4) & 3);  // the chunk that sits at this lane's position
+      const uint32_t vo = (uint32_t)srow * (uint32_t)d * 2u + (uint32_t)echunk * 16u;
       const uint32_t vo16 = vo + 16u * (uint32_t)d * 2u;
       uint16_t* ybase = y + (size_t)cur.row0 * d;
       uint32_t xo_next[2] = {xoff[0], xoff[1]};
@@ -530,10 +540,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           constexpr int b = decltype(Q)::value >> 1, hf = decltype(Q)::value & 1;
           const f32x16 a = acc2[b];
           if ((fr >> 4) == hf) {
-            *reinterpret_cast<uint4*>(epi + epi_wr) = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]),
-                                                                pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
-            *reinterpret_cast<uint4*>(epi + epi_wr + 16) = make_uint4(pack_bf16x2(a[8], a[9]), pack_bf16x2(a[10], a[11]),
-                                                                     pack_bf16x2(a[12], a[13]), pack_bf16x2(a[14], a[15]));
+            *reinterpret_cast<uint4*>(epi + epi_wr0) = make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]),
+                                                                 pack_bf16x2(a[4], a[5]), pack_bf16x2(a[6], a[7]));
+            *reinterpret_cast<uint4*>(epi + epi_wr1) = make_uint4(pack_bf16x2(a[8], a[9]), pack_bf16x2(a[10], a[11]),
+                                                                 pack_bf16x2(a[12], a[13]), pack_bf16x2(a[14], a[15]));
           }
           const uint4 q = *reinterpret_cast<const uint4*>(epi + epi_rd);
           if (srow + 16 * hf < cur.rows) store16<b * 64>(ybase, hf ? vo16 : vo, u32x4{q.x, q.y, q.z, q.w});
