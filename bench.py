@@ -13,6 +13,10 @@ already resident in HBM.  Prints ONE JSON line:
     `kernels_ms_p10`, `kernels_ms_p90`), achieved GB/s and % of HBM peak per stage;
   * ragged-group figures of the batch (`groups`): largest group, m-tiles, rows-per-tile
     histogram, padding of the 256-row tiles and of the 32-row blocks the matrix cores run;
+  * `roofline` names the roof that bounds the dominant kernel at the datasheet peaks (the larger
+    of flops / 2.5 PFLOP/s and algorithmic bytes / 8 TB/s); `roofline_other_roof` is the same
+    launch against the other roof; `ffn_traffic_probe_ms` is the fused kernel run without its
+    matrix products (its memory traffic alone);
   * the FFN's utilisation against the datasheet peak and against the ceilings measured on this
     chip (profiles/microbench_mi355x.txt: matrix cores with random data, from registers / LDS);
   * the CPU oracle timed on a bounded sample of the same workload.
@@ -186,6 +190,24 @@ def main():
         layer_samples.append(e0.elapsed_time(e1))
         for k, (ms, calls) in B.moe_prism_timing_read().items():
             per_kernel[k].append(ms)          # per-step sum (the proxy gate launches some kernels twice)
+    # ---- traffic probe (untimed): the fused kernel's copies, waits, barriers and stores over
+    # the same tile table without the matrix products = the time its memory traffic takes alone
+    probe_ms = None
+    if fused and args.route == "linear":
+        im = B.layer_intermediates(shape, ws)
+        y_probe = torch.empty((wl.T * wl.k_max, wl.d), dtype=B.act_dtype(shape), device="cuda")
+        B.moe_prism_timing_select(["ffn_traffic"])
+        samples = []
+        for i in range(22):
+            B.moe_prism_ffn_traffic_probe(shape, dev["x"], dev["w_gate_up"], dev["w_down"],
+                                          im["group_offset"], im["sorted_pair"], ws, y_probe)
+            torch.cuda.synchronize()
+            ms = B.moe_prism_timing_read()["ffn_traffic"][0]
+            if i >= 2:
+                samples.append(ms)
+        probe_ms = pct(samples, 50)
+        del y_probe
+        B.moe_prism_timing_select(None)
     B.moe_prism_timing_enable(False)
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -233,6 +255,17 @@ def main():
         "pad_waste_pct_32_row_blocks": 100.0 * (1.0 - P / max(float((-(-tiles // 32) * 32).sum()), 1.0)),
     }
 
+    # Which roof bounds the dominant kernel: the larger of its matrix-core time and its HBM time
+    # at the datasheet peaks (a kernel whose arithmetic intensity is below the ridge is HBM-bound).
+    dom_bytes = stage_bytes[dom]
+    dom_gbs = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roof_mfma = {"bound": "mfma", "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                 "frac": dom_tflops / PEAK_BF16_TFLOPS}
+    roof_hbm = {"bound": "hbm", "achieved": dom_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": dom_gbs / PEAK_HBM_GBS}
+    hbm_bound = dom_bytes / PEAK_HBM_GBS > dom_flops / (PEAK_BF16_TFLOPS * 1e3)   # both in 1e-9 s
+    roof, other = (roof_hbm, roof_mfma) if hbm_bound else (roof_mfma, roof_hbm)
+
     peaks = measured_peaks()
     res = {
         "metric": "routed tokens/sec (whole layer, mixed per-request k, 1 GPU); grouped-FFN MFMA util in ffn_mfma_util_pct",
@@ -255,11 +288,13 @@ def main():
         "ffn_mfma_util_pct_measured": {k: 100.0 * ffn_tflops / v for k, v in peaks.items()},
         "ffn_tflops": ffn_tflops,
         "ffn_ms": ffn_ms,
-        "roofline": {"kernel": dom, "bound": "mfma", "achieved": dom_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": dom_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": traffic_bytes(wl.name, dom),
-                     "avg_launch_ms": dom_ms},
+        "roofline": {"kernel": dom, **roof, "traffic": traffic_bytes(wl.name, dom),
+                     "avg_launch_ms": dom_ms, "algorithmic_bytes": dom_bytes,
+                     "algorithmic_flops": dom_flops,
+                     "flop_per_byte": dom_flops / dom_bytes,
+                     "ridge_flop_per_byte": PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS},
+        "roofline_other_roof": other,
+        "ffn_traffic_probe_ms": probe_ms,
         "layer_ms": {"median": pct(layer_samples, 50), "p10": pct(layer_samples, 10),
                      "p90": pct(layer_samples, 90), "samples": n_dist},
         "kernels_ms": kern_med,

@@ -309,7 +309,8 @@ MOE_PRISM_API int moe_prism_status(const void* ws, int32_t* host_flags, int32_t*
 #define MOE_PRISM_K_COMBINE 8
 #define MOE_PRISM_K_PROXY_SELECT 9
 #define MOE_PRISM_K_FFN_FUSED 10 /* gate-up + SwiGLU + down in one kernel (narrow sub-experts) */
-#define MOE_PRISM_N_KERNELS 11
+#define MOE_PRISM_K_FFN_TRAFFIC 11 /* moe_prism_ffn_traffic_probe */
+#define MOE_PRISM_N_KERNELS 12
 MOE_PRISM_API int moe_prism_timing_enable(int on);
 MOE_PRISM_API int moe_prism_timing_select(uint32_t kernel_mask);
 MOE_PRISM_API int moe_prism_timing_read(float* ms, int32_t* calls);
@@ -332,6 +333,21 @@ typedef struct {
 } moe_prism_microbench_result;
 MOE_PRISM_API int moe_prism_microbench(int32_t max_results, moe_prism_microbench_result* results,
                                        int32_t* n_results);
+
+/*
+ * Traffic probe of the fused grouped-FFN kernel (measurement only; no passage of the
+ * paper).  Same arguments and checks as moe_prism_grouped_ffn; launches that kernel's
+ * copies, barriers, waits, operand reads and output stores over the same tile table with
+ * the matrix products left out, so its duration (kernel id MOE_PRISM_K_FFN_TRAFFIC) is the
+ * time the kernel's memory traffic takes by itself.  The rows of y it writes hold no
+ * meaningful values.  MOE_PRISM_ERR_UNSUPPORTED_SHAPE for shapes the fused kernel does not
+ * serve (moe_prism_grouped_ffn runs its two-kernel path there).
+ */
+MOE_PRISM_API int moe_prism_ffn_traffic_probe(const moe_prism_shape* shape, const void* x,
+                                              const void* w_gate_up, const void* w_down,
+                                              const int32_t* group_offset,
+                                              const int32_t* sorted_pair, void* y, void* ws,
+                                              size_t ws_bytes, void* stream);
 
 MOE_PRISM_API const char* moe_prism_strerror(int code);
 

@@ -16,7 +16,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmoe_prism.so")
 
 KERNEL_NAMES = ("logits", "topk", "dispatch_count", "dispatch_scan", "dispatch_place",
-                "ffn_tiles", "ffn_gate_up", "ffn_down", "combine", "proxy_select", "ffn_fused")
+                "ffn_tiles", "ffn_gate_up", "ffn_down", "combine", "proxy_select", "ffn_fused",
+                "ffn_traffic")
 
 EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_dispatch", "moe_prism_grouped_ffn", "moe_prism_combine", "moe_prism_layer",
@@ -25,6 +26,7 @@ EXPORTS = ("moe_prism_workspace_bytes", "moe_prism_expand_k", "moe_prism_route",
            "moe_prism_partition_greedy", "moe_prism_partition_objective", "moe_prism_partition_anneal",
            "moe_prism_layer_offsets", "moe_prism_status", "moe_prism_timing_enable",
            "moe_prism_timing_select", "moe_prism_timing_read", "moe_prism_microbench",
+           "moe_prism_ffn_traffic_probe",
            "moe_prism_strerror")
 
 
@@ -139,6 +141,14 @@ def moe_prism_grouped_ffn(shape, x, w_gate_up, w_down, group_offset, sorted_pair
                                        _ptr(group_offset), _ptr(sorted_pair), _ptr(y), _ptr(ws),
                                        C.c_size_t(ws.numel()), _stream()))
     return y
+
+
+def moe_prism_ffn_traffic_probe(shape, x, w_gate_up, w_down, group_offset, sorted_pair, ws, y):
+    """The fused FFN kernel's memory operations alone (timed as kernel "ffn_traffic"); y is
+    overwritten with values that mean nothing."""
+    _check(lib().moe_prism_ffn_traffic_probe(C.byref(shape), _ptr(x), _ptr(w_gate_up), _ptr(w_down),
+                                             _ptr(group_offset), _ptr(sorted_pair), _ptr(y),
+                                             _ptr(ws), C.c_size_t(ws.numel()), _stream()))
 
 
 def moe_prism_combine(shape, y, slot_of_pair, topk_w, k_tok, out=None):

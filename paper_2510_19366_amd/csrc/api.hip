@@ -166,13 +166,21 @@ static bool use_fused_ffn(const moe_prism_shape* s) {
 
 static int do_ffn(const moe_prism_shape* s, const Layout& L, const void* x, const void* w_gu,
                   const void* w_dn, const int32_t* off, const int32_t* sorted_pair, void* y,
-                  char* ws, hipStream_t st) {
+                  char* ws, hipStream_t st, bool traffic_probe = false) {
   const int E = s->n_experts * s->n_sub;
   int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
   MTile* tiles = reinterpret_cast<MTile*>(ws + L.tiles);
   void* h = ws + L.h;
   MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(off, tiles, hdr, E, L.max_mtiles, s->T * s->k_max, st));
   if (s->T == 0) return MOE_PRISM_OK;
+  if (traffic_probe) {
+    MP_LAUNCH(MOE_PRISM_K_FFN_TRAFFIC,
+              launch_ffn_fused_traffic_bf16((const uint16_t*)x, (const uint16_t*)w_gu,
+                                            (const uint16_t*)w_dn, sorted_pair, tiles, hdr,
+                                            (uint16_t*)y, s->T, s->d, s->inter_sub, s->k_max,
+                                            L.max_mtiles, st));
+    return MOE_PRISM_OK;
+  }
   if (use_fused_ffn(s)) {
     MP_LAUNCH(MOE_PRISM_K_FFN_FUSED,
               launch_ffn_fused_bf16((const uint16_t*)x, (const uint16_t*)w_gu, (const uint16_t*)w_dn,
@@ -338,6 +346,22 @@ int moe_prism_grouped_ffn(const moe_prism_shape* shape, const void* x, const voi
   MP_CHECK_WS(shape, L, ws, ws_bytes);
   return do_ffn(shape, L, x, w_gate_up, w_down, group_offset, sorted_pair, y,
                 static_cast<char*>(ws), (hipStream_t)stream);
+}
+
+int moe_prism_ffn_traffic_probe(const moe_prism_shape* shape, const void* x, const void* w_gate_up,
+                                const void* w_down, const int32_t* group_offset,
+                                const int32_t* sorted_pair, void* y, void* ws, size_t ws_bytes,
+                                void* stream) {
+  MP_CHECK_SHAPE(shape);
+  if (w_gate_up == nullptr || w_down == nullptr || group_offset == nullptr)
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->T > 0 && (x == nullptr || sorted_pair == nullptr || y == nullptr))
+    return MOE_PRISM_ERR_INVALID_ARG;
+  if (shape->dtype != MOE_PRISM_BF16 || !mp::ffn_fused_supported(shape->T, shape->d, shape->inter_sub))
+    return MOE_PRISM_ERR_UNSUPPORTED_SHAPE;
+  MP_CHECK_WS(shape, L, ws, ws_bytes);
+  return do_ffn(shape, L, x, w_gate_up, w_down, group_offset, sorted_pair, y,
+                static_cast<char*>(ws), (hipStream_t)stream, true);
 }
 
 int moe_prism_combine(const moe_prism_shape* shape, const void* y, const int32_t* slot_of_pair,

@@ -179,7 +179,22 @@ struct TileHdr {  // wave-uniform
   int g, row0, rows;
 };
 
-template <int IS>
+// One matrix-core step.  MATH = false is the traffic probe: the same operand reads, copies,
+// barriers, waits and stores, with one cheap ALU operation in place of the multiply (the
+// fragments stay live, the results mean nothing).
+template <bool MATH>
+__device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
+  if constexpr (MATH) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  } else {
+    const uint4 u = __builtin_bit_cast(uint4, a), v = __builtin_bit_cast(uint4, b);
+    c[0] += __uint_as_float((u.x ^ v.x) & 0x3fffffffu);
+    c[5] += __uint_as_float((u.w ^ v.y) & 0x3fffffffu);
+    return c;
+  }
+}
+
+template <int IS, bool MATH>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void ffn_fused_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_gu,
     const uint16_t* __restrict__ w_dn, const int32_t* __restrict__ sorted_pair,
@@ -443,7 +458,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int i = 0; i < STEPS; ++i) {
-            acc1[i % NBLK] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i % PD], xa[i / NBLK], acc1[i % NBLK], 0, 0, 0);
+            acc1[i % NBLK] = mma<MATH>(wf[i % PD], xa[i / NBLK], acc1[i % NBLK]);
             wf[i % PD] = i + PD < STEPS ? rd_w1f(c_w, i + PD) : rd_w1f(nw, i + PD - STEPS);
             __builtin_amdgcn_sched_barrier(0);
             if (i == B_STEP) {
@@ -520,7 +535,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < STEPS; ++i) {
-          acc2[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wd[i % PD], hfrag[i >> 1], acc2[i & 1], 0, 0, 0);
+          acc2[i & 1] = mma<MATH>(wd[i % PD], hfrag[i >> 1], acc2[i & 1]);
           wd[i % PD] = i + PD < STEPS ? rd_w2f(c_w, i + PD) : rd_w2f(nw, i + PD - STEPS);
           __builtin_amdgcn_sched_barrier(0);
           if (i == B_STEP) {
@@ -567,21 +582,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   }
 }
 
-template <int IS>
+template <int IS, bool MATH>
 static hipError_t launch_is(const uint16_t* x, const uint16_t* w_gu, const uint16_t* w_dn,
                             const int32_t* sorted_pair, const MTile* tiles, int32_t* hdr,
                             uint16_t* y, int T, int d, int k_max, int max_mtiles, hipStream_t s) {
-  static bool done[64] = {};
+  static bool done[64] = {};  // per instantiation (IS, MATH)
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
   if (dev < 0 || !done[dev]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_fused_kernel<IS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_fused_kernel<IS, MATH>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg<IS>::LDS_BYTES);
     if (e != hipSuccess) return e;
     if (dev >= 0) done[dev] = true;
   }
   const int grid = persistent_grid(max_mtiles, 1);
-  ffn_fused_kernel<IS><<<grid, NT, Cfg<IS>::LDS_BYTES, s>>>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y,
+  ffn_fused_kernel<IS, MATH><<<grid, NT, Cfg<IS>::LDS_BYTES, s>>>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y,
                                                             T, d, k_max);
   return hipGetLastError();
 }
@@ -599,17 +614,33 @@ bool ffn_fused_supported(int T, int d, int Is) {
   return true;
 }
 
+template <bool MATH>
+static hipError_t launch_fused(const uint16_t* x, const uint16_t* w_gu, const uint16_t* w_dn,
+                               const int32_t* sorted_pair, const MTile* tiles, int32_t* hdr,
+                               uint16_t* y, int T, int d, int Is, int k_max, int max_mtiles,
+                               hipStream_t s) {
+  if (max_mtiles <= 0) return hipSuccess;
+  switch (Is) {
+    case 64: return fused::launch_is<64, MATH>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, k_max, max_mtiles, s);
+    case 128: return fused::launch_is<128, MATH>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, k_max, max_mtiles, s);
+    case 192: return fused::launch_is<192, MATH>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, k_max, max_mtiles, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_ffn_fused_bf16(const uint16_t* x, const uint16_t* w_gu, const uint16_t* w_dn,
                                  const int32_t* sorted_pair, const MTile* tiles, int32_t* hdr,
                                  uint16_t* y, int T, int d, int Is, int k_max, int max_mtiles,
                                  hipStream_t s) {
-  if (max_mtiles <= 0) return hipSuccess;
-  switch (Is) {
-    case 64: return fused::launch_is<64>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, k_max, max_mtiles, s);
-    case 128: return fused::launch_is<128>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, k_max, max_mtiles, s);
-    case 192: return fused::launch_is<192>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, k_max, max_mtiles, s);
-    default: return hipErrorInvalidValue;
-  }
+  return launch_fused<true>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, Is, k_max, max_mtiles, s);
+}
+
+// The kernel's memory operations alone (see mma<false>): what y holds afterwards means nothing.
+hipError_t launch_ffn_fused_traffic_bf16(const uint16_t* x, const uint16_t* w_gu,
+                                         const uint16_t* w_dn, const int32_t* sorted_pair,
+                                         const MTile* tiles, int32_t* hdr, uint16_t* y, int T,
+                                         int d, int Is, int k_max, int max_mtiles, hipStream_t s) {
+  return launch_fused<false>(x, w_gu, w_dn, sorted_pair, tiles, hdr, y, T, d, Is, k_max, max_mtiles, s);
 }
 
 }  // namespace mp

@@ -63,6 +63,11 @@ hipError_t launch_ffn_fused_bf16(const uint16_t* x, const uint16_t* w_gu, const 
                                  const int32_t* sorted_pair, const MTile* tiles, int32_t* hdr,
                                  uint16_t* y, int T, int d, int Is, int k_max, int max_mtiles,
                                  hipStream_t s);
+// the same kernel without the matrix products (measurement: its memory traffic alone)
+hipError_t launch_ffn_fused_traffic_bf16(const uint16_t* x, const uint16_t* w_gu,
+                                         const uint16_t* w_dn, const int32_t* sorted_pair,
+                                         const MTile* tiles, int32_t* hdr, uint16_t* y, int T,
+                                         int d, int Is, int k_max, int max_mtiles, hipStream_t s);
 
 hipError_t launch_combine(int dtype, const void* y, const int32_t* slot_of_pair, const float* w,
                           const int32_t* k_tok, void* out, int T, int d, int k_max, hipStream_t s);

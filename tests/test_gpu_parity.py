@@ -106,6 +106,41 @@ def test_narrow_sub_experts_both_ffn_paths(case, path, monkeypatch):
         ((1, 0, 0) if path == "fused" else (0, 1, 1))
 
 
+def test_traffic_probe_runs_beside_the_ffn_and_leaves_it_alone():
+    # the measurement entry point walks the same tile table with the products left out: it
+    # must stay inside y's rows [0, P) (guard rows and the rows >= P keep their fill), refuse
+    # shapes the fused kernel does not serve, and leave the tables so that the next FFN call
+    # still gives the result it gave before
+    wl = W.make_workload("probe", dtype="bf16", d=512, n_experts=12, n_sub=4, inter_sub=192,
+                         req_tokens=[1] * 1500, req_k=np.random.default_rng(5).integers(0, 9, 1500).astype(np.int32),
+                         k_max=8, seed=5, bias_std=1.0, w_std=0.05)
+    r = run_stages(wl)
+    dev, ws, shape = r["dev"], r["ws"], r["shape"]
+    P = int(r["off"][-1])
+    off = torch.from_numpy(r["off"]).cuda()
+    sp = torch.from_numpy(r["sorted_pair"]).cuda()
+    y = torch.full((wl.T * wl.k_max, wl.d), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.moe_prism_timing_enable(True)
+    B.moe_prism_timing_read()
+    B.moe_prism_ffn_traffic_probe(shape, dev["x"], dev["w_gate_up"], dev["w_down"], off, sp, ws, y)
+    torch.cuda.synchronize()
+    t = B.moe_prism_timing_read()
+    B.moe_prism_timing_enable(False)
+    assert t["ffn_traffic"][1] == 1 and t["ffn_fused"][1] == 0
+    assert P < wl.T * wl.k_max and bool((y[P:] == 7.0).all())
+    y2 = B.moe_prism_grouped_ffn(shape, dev["x"], dev["w_gate_up"], dev["w_down"], off, sp, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(y2[:P]), r["y"])
+    wide = W.make_workload("wide", dtype="bf16", d=256, n_experts=4, n_sub=1, inter_sub=256,
+                           req_tokens=[40], req_k=[2], k_max=2, seed=1)
+    rw = run_stages(wide)
+    with pytest.raises(B.MoePrismError):
+        B.moe_prism_ffn_traffic_probe(rw["shape"], rw["dev"]["x"], rw["dev"]["w_gate_up"],
+                                      rw["dev"]["w_down"], torch.from_numpy(rw["off"]).cuda(),
+                                      torch.from_numpy(rw["sorted_pair"]).cuda(), rw["ws"],
+                                      torch.empty((80, 256), dtype=torch.bfloat16, device="cuda"))
+
+
 def test_no_renormalize_and_repeated_rows():
     # repeated-row router: exact S-way ties decided by id; full-softmax weights
     base = W.make_workload("a", dtype="bf16", d=128, n_experts=16, n_sub=1, inter_sub=128,
