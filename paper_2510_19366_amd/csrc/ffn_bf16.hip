@@ -17,6 +17,9 @@
 // double-buffered, XOR-swizzled LDS tile, one slab ahead of the MFMAs.
 // Narrow sub-experts (Is in {64, 128, 192}) take the fused kernel in ffn_fused_bf16.hip
 // instead; these two kernels serve every other shape.
+#include <cstdlib>
+#include <type_traits>
+
 #include "ffn_common.h"
 
 namespace mp {
@@ -257,6 +260,23 @@ struct GateUpOp {
     const int tok = pair_lds[r] / k_max;
     return x + (size_t)min(max(tok, 0), T - 1) * d;
   }
+  // the same rows as a wave-uniform base plus a 32-bit byte offset per row (K = 64 driver)
+  __device__ __forceinline__ void bases(const Sc& sc, const uint16_t*& ba, const uint16_t*& bb) const {
+    ba = x;
+    bb = w_gu + (size_t)sc.g * 2 * Is * d;
+  }
+  __device__ __forceinline__ uint32_t a_off(const Sc&, int r, const int32_t* pair_lds) const {
+    const int tok = pair_lds[r] / k_max;
+    return (uint32_t)min(max(tok, 0), T - 1) * (uint32_t)d * 2u;
+  }
+  __device__ __forceinline__ uint32_t b_off(const Sc& it, int br) const {
+    const int blk = br >> 5, rr = br & 31;
+    const int neuron = min(it.n0 + blk * 16 + (rr & 15), Is - 1);
+    return (uint32_t)((rr >> 4) ? Is + neuron : neuron) * (uint32_t)d * 2u;
+  }
+  static bool offsets_fit(long T, long d, long Is) {
+    return T * d * 2 < (1L << 32) && 2 * Is * d * 2 < (1L << 32);
+  }
   __device__ __forceinline__ const uint16_t* b_row(const Sc& it, int br) const {
     const int blk = br >> 5, rr = br & 31;  // 32-row block of the tile, row inside it
     const int neuron = min(it.n0 + blk * 16 + (rr & 15), Is - 1);
@@ -345,6 +365,17 @@ struct DownOp {
   __device__ __forceinline__ const uint16_t* a_src(const Sc& sc, int r, const int32_t*) const {
     return h + (size_t)(sc.row0 + min(r, sc.rows - 1)) * Is;
   }
+  __device__ __forceinline__ void bases(const Sc& sc, const uint16_t*& ba, const uint16_t*& bb) const {
+    ba = h + (size_t)sc.row0 * Is;
+    bb = w_dn + (size_t)sc.g * d * Is;
+  }
+  __device__ __forceinline__ uint32_t a_off(const Sc& sc, int r, const int32_t*) const {
+    return (uint32_t)min(r, sc.rows - 1) * (uint32_t)Is * 2u;
+  }
+  __device__ __forceinline__ uint32_t b_off(const Sc& it, int br) const {
+    return (uint32_t)min(it.n0 + br, d - 1) * (uint32_t)Is * 2u;
+  }
+  static bool offsets_fit(long, long d, long Is) { return d * Is * 2 < (1L << 32); }
   __device__ __forceinline__ const uint16_t* b_row(const Sc& it, int br) const {
     return w_dn + ((size_t)it.g * d + min(it.n0 + br, d - 1)) * Is;
   }
@@ -844,6 +875,303 @@ __global__ __launch_bounds__(NT_) void down_bf16_dma_kernel(DownOp<BN> op,
   run_items_dma<BN, DownOp<BN>, PP>(op, tiles, hdr, op.Is, n_tiles_n, HDR_DYN_DOWN);
 }
 
+// ---------------------------------------------------------------- K = 64 driver
+// The caches of this chip move whole 128-byte lines: a copy that asks for 64 bytes of a row
+// (a K stage of 32 elements) pulls the line from L2 into L1 all the same, and when the other
+// half is wanted a stage later the line has left the 32 KiB L1 again, so the L2 -> L1 path
+// carries every byte twice (measured: copies that touch only half of each line reach half the
+// bandwidth at every level of the hierarchy).  With wide sub-experts that path is what the
+// kernels above wait for.  This driver therefore works in stages of 64 K-elements, 128 bytes
+// per row and copy: 8 lanes of a copy instruction fetch one whole line.
+//   * Ring of 2 stages of (256 + BN) rows x 128 bytes (128 KiB for BN = 256).
+//   * All waves run the same instruction stream; per stage a wave issues 4 K steps of 2 x NB
+//     MFMAs, and the fragments of step i + 1 are read from LDS while step i is multiplied
+//     (sched_barriers pin that interleaving), across stage and item borders.
+//   * One s_barrier per stage, three quarters into it: by then a wave has read its last
+//     fragments of stage q and has waited for its own copies of stage q + 1, so the barrier
+//     both frees the slot of stage q and publishes stage q + 1; the copies of stage q + 2 go
+//     out right behind it and have one whole stage of flight.
+//   * Vector memory operations retire in issue order, so "my copies of stage q + 1 have landed"
+//     is s_waitcnt vmcnt(n) with n = what this wave issued after them (an epilogue's stores,
+//     a slot-list fetch), bounded from below.
+constexpr int SK2 = 64;
+template <int BN, bool GATHER>
+struct Ring64 {
+  static constexpr int NB = BN / 2 / 32;
+  static constexpr int WB = BN / 64;  // copy instructions (8 rows x 128 bytes) per wave and stage, weight rows
+  static constexpr int A_ST = BM * SK2, B_ST = BN * SK2, STAGE = A_ST + B_ST;  // elements
+  static constexpr size_t RING_BYTES = 2 * (size_t)STAGE * 2;
+  static constexpr size_t PAIR_BYTES = GATHER ? 2 * BM * sizeof(int32_t) : 0;
+  static constexpr size_t EPI_BYTES = GATHER ? 0 : (NT_ / 64) * EPI_WAVE_BYTES;
+  static constexpr size_t LDS_BYTES = RING_BYTES + PAIR_BYTES + EPI_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS per CU");
+};
+
+// N copies of one wave: lane i's 16 bytes at base + voff[j] land at lds + 1024 j + 16 i
+template <int N>
+__device__ __forceinline__ void dma16_rows(const void* base, const uint32_t (&voff)[N], uint32_t lds) {
+  static_assert(N == 3 || N == 4, "copies per group");
+  uint32_t keep;
+  if constexpr (N == 3) {
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %5\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %4\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %4\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %3, %4\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "s"(base), "s"(lds)
+        : "memory", "scc");
+  } else {
+    asm volatile(
+        "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %6\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, %5\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %2, %5\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %3, %5\n\ts_add_u32 m0, m0, 0x400\n\ts_nop 0\n\t"
+        "global_load_lds_dwordx4 %4, %5\n\ts_mov_b32 m0, %0"
+        : "=&s"(keep)
+        : "v"(voff[0]), "v"(voff[1]), "v"(voff[2]), "v"(voff[3]), "s"(base), "s"(lds)
+        : "memory", "scc");
+  }
+}
+// until at most n of this wave's vector memory operations are pending (n wave-uniform; the
+// count is an immediate of s_waitcnt, so n selects one instruction by bisection)
+template <int LO, int HI>
+__device__ __forceinline__ void wait_upto(int n) {
+  if constexpr (LO == HI) {
+    wait_copies<LO>();
+  } else {
+    constexpr int MID = (LO + HI + 1) / 2;
+    if (n >= MID)
+      wait_upto<MID, HI>(n);
+    else
+      wait_upto<LO, MID - 1>(n);
+  }
+}
+// which 16-byte chunk of a 128-byte row sits at position pos (inverse of swz)
+template <int MODE>
+__device__ __forceinline__ int chunk64_of(int r, int pos) {
+  const int f = MODE == SWZ_SEQ ? ((r >> 1) & 7) : (((r >> 1) & 3) | (((r >> 4) & 1) << 2));
+  return pos ^ f;
+}
+
+template <int BN, class Op>
+__device__ __forceinline__ void run_items_k64(const Op& op, const MTile* __restrict__ tiles,
+                                              int32_t* __restrict__ hdr, int K, int n_tiles_n,
+                                              int dyn_word) {
+  using RG = Ring64<BN, Op::GATHER>;
+  constexpr int NB = RG::NB, WB = RG::WB;
+  constexpr int NM = 2 * NB;      // MFMAs per K step
+  constexpr int NF = 2 + NB;      // fragments per K step
+  extern __shared__ __align__(16) uint16_t smem[];
+  int32_t* pair_lds = reinterpret_cast<int32_t*>(smem + 2 * (size_t)RG::STAGE);  // [2][BM]
+  const int lane = threadIdx.x & 63, wv = uni(threadIdx.x >> 6);
+  uint16_t* epi_lds = RG::EPI_BYTES ? smem + (RG::RING_BYTES + RG::PAIR_BYTES) / 2 + (size_t)wv * (EPI_WAVE_BYTES / 2) : nullptr;
+  const int wm = wv >> 1, wn = wv & 1;
+  const int wrow = Op::wrow(lane & 31);
+  // work split and item order: as in run_items_dma
+  int32_t* dyn_next = reinterpret_cast<int32_t*>(smem);
+  const int total_items = hdr[HDR_MTILES] * n_tiles_n;
+  const int n_static = total_items - total_items / DYN_DIV;
+  const int nst = K / SK2;  // K % 64 == 0 on this path
+  const int batch = nst >= 12 ? 1 : (12 + nst - 1) / nst;
+  ItemRange ir = xcd_items(n_static);
+  int n_my = ir.begin < ir.end ? (ir.end - ir.begin + ir.step - 1) / ir.step : 0;
+  const uint32_t smem_base = lds_addr(smem);
+  const uint32_t pair_base = lds_addr(pair_lds);
+  const int sub = lane >> 3, pos = lane & 7;  // a copy covers 8 rows: row lane / 8, position lane % 8
+
+  Sc cur, nxt;
+  auto load_sc = [&](int my_idx, Sc& sc) {
+    const int item = ir.begin + my_idx * ir.step;
+    const MTile t0 = tiles[item / n_tiles_n];
+    const int first = uni(t0.first), cnt = uni(t0.count);
+    const int L = item - first * n_tiles_n;
+    int C = 32 / (cnt < 6 ? cnt : 6);
+    C = C > n_tiles_n ? n_tiles_n : C;
+    const int per = cnt * C;
+    const int c = L / per, r = L % per;
+    const int Cc = min(C, n_tiles_n - c * C);
+    op.setup_sc(tiles[first + r / Cc], c * C + r % Cc, sc);
+  };
+  auto fetch_pairs = [&](const Sc& sc, int parity) -> int {
+    if (Op::GATHER && wv < 4) {
+      dma4(op.idx_src(sc, wv * 64 + lane), pair_base + (uint32_t)(parity * BM + wv * 64) * 4);
+      return 1;
+    }
+    return 0;
+  };
+  // producer: uniform bases that advance 64 elements per stage, byte offsets of this lane's rows
+  const uint16_t* pa;
+  const uint16_t* pb;
+  uint32_t va[4], vb[WB];
+  auto producer_rows = [&](const Sc& sc, int parity) {
+    op.bases(sc, pa, pb);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = wv * 32 + j * 8 + sub;
+      va[j] = op.a_off(sc, r, pair_lds + parity * BM) + (uint32_t)chunk64_of<SWZ_SEQ>(r, pos) * 16u;
+    }
+#pragma unroll
+    for (int j = 0; j < WB; ++j) {
+      const int br = (wv * WB + j) * 8 + sub;
+      vb[j] = op.b_off(sc, br) + (uint32_t)chunk64_of<Op::WSWZ>(br, pos) * 16u;
+    }
+  };
+  auto issue_stage = [&](int slot) {
+    const uint32_t sa = smem_base + (uint32_t)slot * (RG::STAGE * 2);
+    const uint32_t sb = sa + RG::A_ST * 2;
+    dma16_rows<4>(pa, va, sa + (uint32_t)wv * 4096u);
+    dma16_rows<WB>(pb, vb, sb + (uint32_t)(wv * WB) * 1024u);
+    pa += SK2;
+    pb += SK2;
+  };
+
+  struct Frag {
+    bf16x8 t[2], w[NB];
+  };
+  // fragment e (0, 1: slot-row blocks; 2..: weight blocks) of K step ks of ring slot `slot`
+  auto read_frag = [&](int slot, int ks, int e) -> bf16x8 {
+    const uint16_t* sa = smem + (size_t)slot * RG::STAGE;
+    const int c = ks * 2 + (lane >> 5);
+    if (e < 2) return *reinterpret_cast<const bf16x8*>(sa + swz<SWZ_SEQ>(wm * 64 + e * 32 + (lane & 31), c));
+    return *reinterpret_cast<const bf16x8*>(sa + RG::A_ST + swz<Op::WSWZ>(wn * (BN / 2) + (e - 2) * 32 + wrow, c));
+  };
+  auto put_frag = [&](Frag& f, int e, bf16x8 v) {
+    if (e < 2) f.t[e] = v; else f.w[e - 2] = v;
+  };
+
+  for (;;) {
+  if (n_my > 0) {
+    const int total = n_my * nst;
+    // ---- prologue of one pipeline run over n_my items
+    load_sc(0, cur);
+    nxt = cur;
+    if (n_my > 1) load_sc(1, nxt);
+    fetch_pairs(cur, 0);
+    wait_copies<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    producer_rows(cur, 0);
+    if (n_my > 1) fetch_pairs(nxt, 1);
+    int p = 0, p_stage = 0, p_item = 0;  // producer: stages issued, stage inside its item, item
+    auto produce = [&]() -> int {       // the next stage's copies, into slot p & 1
+      if (p >= total) return 0;
+      if (p_stage == nst) {  // the producer enters the next item
+        p_stage = 0;
+        ++p_item;
+        producer_rows(nxt, p_item & 1);
+      }
+      issue_stage(p & 1);
+      ++p;
+      ++p_stage;
+      return 4 + WB;
+    };
+    produce();                       // stage 0
+    const int second = produce();    // stage 1 (nst >= 2)
+    wait_upto<0, 8>(second);         // stage 0 and the slot-list fetch have landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    f32x16 acc[NB][2];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+    int mb_on = (cur.rows - wm * 64 + 31) / 32;
+    mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+
+    Frag f0, f1;
+#pragma unroll
+    for (int e = 0; e < NF; ++e) put_frag(f0, e, read_frag(0, 0, e));
+    int c_stage = 0, c_item = 0;
+    int n_allow = 0;  // operations issued after the copies of the stage the next wait is for
+    // One K step: the MFMAs of `use`; behind MFMA i the fragment i of (slot_f, ks_f) is read into
+    // `fill`.  HOOK: after the first MFMA the stage's wait, barrier and copy issue.
+    auto kstep = [&](const Frag& use, Frag& fill, int slot_f, int ks_f, auto on, auto&& hook) {
+#pragma unroll
+      for (int m = 0; m < NM; ++m) {
+        const int mb = m / NB, nb = m % NB;
+        if constexpr (decltype(on)::value)
+          acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(use.w[nb], use.t[mb], acc[nb][mb], 0, 0, 0);
+        if (m == 0) hook();
+        if (m < NF) put_frag(fill, m, read_frag(slot_f, ks_f, m));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto nohook = [] {};
+    auto stage = [&](int slot, auto on) {
+      __builtin_amdgcn_sched_barrier(0);
+      kstep(f0, f1, slot, 1, on, nohook);
+      kstep(f1, f0, slot, 2, on, nohook);
+      kstep(f0, f1, slot, 3, on, nohook);
+      kstep(f1, f0, slot ^ 1, 0, on, [&] {
+        // every fragment of stage q is in registers (the MFMA above needed the last ones)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        wait_upto<0, 24>(n_allow);       // this wave's copies of stage q + 1 have landed
+        n_allow = 0;
+        __builtin_amdgcn_s_barrier();    // frees the slot of stage q, publishes stage q + 1
+        asm volatile("" ::: "memory");
+        produce();                       // stage q + 2 into the slot of stage q
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+    for (int q = 0; q < total; ++q) {
+      // a wave whose 64 slot rows are all beyond the tile's rows multiplies nothing
+      if (mb_on > 0)
+        stage(q & 1, std::true_type{});
+      else
+        stage(q & 1, std::false_type{});
+      if (++c_stage == nst) {  // the item is complete
+        op.epilogue(cur, acc, mb_on, epi_lds);
+        n_allow += uni(op.stores_issued(cur, mb_on, wm, wn));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.0f;
+        c_stage = 0;
+        ++c_item;
+        cur = nxt;
+        mb_on = (cur.rows - wm * 64 + 31) / 32;
+        mb_on = uni(mb_on < 0 ? 0 : (mb_on > 2 ? 2 : mb_on));
+        if (c_item + 1 < n_my) {
+          load_sc(c_item + 1, nxt);
+          n_allow += fetch_pairs(nxt, (c_item + 1) & 1);
+        }
+      }
+    }
+  }
+    // ---- next batch from the pool (every copy of this run has landed, every wave is here)
+    wait_copies<0>();
+    __syncthreads();
+    if (threadIdx.x == 0) *dyn_next = atomicAdd(&hdr[dyn_word], batch);
+    __syncthreads();
+    ir.begin = n_static + uni(*dyn_next);
+    if (ir.begin >= total_items) break;
+    ir.end = min(total_items, ir.begin + batch);
+    ir.step = 1;
+    n_my = ir.end - ir.begin;
+  }
+}
+
+template <int BN>
+__global__ __launch_bounds__(NT_) void gate_up_bf16_k64_kernel(GateUpOp<BN> op,
+                                                               const MTile* __restrict__ tiles,
+                                                               int32_t* __restrict__ hdr,
+                                                               int n_tiles_n) {
+  run_items_k64<BN, GateUpOp<BN>>(op, tiles, hdr, op.d, n_tiles_n, HDR_DYN_GATE_UP);
+}
+template <int BN>
+__global__ __launch_bounds__(NT_) void down_bf16_k64_kernel(DownOp<BN> op,
+                                                            const MTile* __restrict__ tiles,
+                                                            int32_t* __restrict__ hdr,
+                                                            int n_tiles_n) {
+  run_items_k64<BN, DownOp<BN>>(op, tiles, hdr, op.Is, n_tiles_n, HDR_DYN_DOWN);
+}
+
 // ---------------------------------------------------------------- launchers
 // The tiles need more than the default 64 KiB of dynamic LDS (the CU has 160 KiB).  The
 // attribute is set once per kernel and device, so the launch path makes no other runtime call
@@ -879,6 +1207,14 @@ static hipError_t launch_persistent(const Op& op, size_t lds_bytes, int grid, co
 // Items with at least this many K stages run the two-group schedule; with fewer, the epilogues
 // dominate and the in-step schedule is faster (measured at K = 192: 6 stages per item).
 constexpr int PP_MIN_STAGES = 12;
+// The K = 64 driver needs a few stages per item (its producer runs two stages ahead and enters
+// at most one new item per stage).  MOE_PRISM_FFN_K=32 forces the 32-element stages (A/B
+// measurements; tests run both drivers on the same shapes).
+constexpr int K64_MIN_STAGES = 4;
+static bool force_k32() {
+  const char* e = getenv("MOE_PRISM_FFN_K");
+  return e != nullptr && e[0] == '3' && e[1] == '2' && e[2] == 0;
+}
 
 template <int BN>
 static hipError_t launch_gate_up_bn(const GateUpOp<BN>& op, int max_mtiles, const MTile* tiles,
@@ -887,6 +1223,10 @@ static hipError_t launch_gate_up_bn(const GateUpOp<BN>& op, int max_mtiles, cons
   const int ntn = cdiv(op.Is, BN / 2);
   const int grid = persistent_grid((long)max_mtiles * ntn, 1);
   const int nst = op.d / SK;
+  // stages of 64 K-elements (whole cache lines per row): d % 64 == 0 always; at least 4 stages
+  // per item, 32-bit byte offsets inside x and inside one sub-expert's weights
+  if (op.d / SK2 >= K64_MIN_STAGES && GateUpOp<BN>::offsets_fit(op.T, op.d, op.Is) && !force_k32())
+    return launch_persistent<gate_up_bf16_k64_kernel<BN>>(op, Ring64<BN, true>::LDS_BYTES, grid, tiles, hdr, ntn, s);
   // the ring needs the next tile's slot-list entries one item ahead, published by a barrier
   // before any wave uses them: K/32 >= 2 D stages per item
   if (nst >= 2 * RG::D && nst >= PP_MIN_STAGES)
@@ -911,6 +1251,8 @@ static hipError_t launch_down_bn(const DownOp<BN>& op, int max_mtiles, const MTi
   const int ntn = cdiv(op.d, BN);
   const int grid = persistent_grid((long)max_mtiles * ntn, 1);
   const int nst = op.Is / SK;
+  if (op.Is % SK2 == 0 && op.Is / SK2 >= K64_MIN_STAGES && DownOp<BN>::offsets_fit(0, op.d, op.Is) && !force_k32())
+    return launch_persistent<down_bf16_k64_kernel<BN>>(op, Ring64<BN, false>::LDS_BYTES, grid, tiles, hdr, ntn, s);
   // the ring keeps D stages in flight inside one item or the next: K/32 >= NS stages per item
   if (nst >= RG::NS && nst >= PP_MIN_STAGES)
     return launch_persistent<down_bf16_dma_kernel<BN, true>>(op, RG::LDS_BYTES, grid, tiles, hdr, ntn, s);

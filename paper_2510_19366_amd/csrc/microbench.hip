@@ -157,7 +157,10 @@ __device__ __forceinline__ void wait_vm() {
 // pattern) of rows `row_stride` bytes apart out of a region of `footprint` bytes, DEPTH
 // copies in flight.  TO_LDS: global_load_lds_dwordx4; else 16-byte loads into registers.
 // layout 0: 4 adjacent lanes share a row (coalesced 64-byte runs); layout 1: every lane
-// its own row, 32 rows x two 16-byte halves (the MFMA operand layout read straight from memory).
+// its own row, 32 rows x two 16-byte halves (the MFMA operand layout read straight from memory);
+// layout 2: like 0, but a wave steps 128 bytes along the row, so only the first 64 bytes of
+// every 128-byte line are ever requested (what a K stage of 32 bf16 elements asks of the
+// caches when the other half of the line is needed a stage later).
 template <int DEPTH, int NW, bool TO_LDS>
 __global__ __launch_bounds__(NW * 64) void stream_kernel(const char* __restrict__ src,
                                                          size_t footprint, int iters,
@@ -171,11 +174,11 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const char* __restrict_
   // a wave walks whole row blocks (rows x row_stride bytes) and then moves on by the number
   // of waves in the grid, so the grid streams through the entire footprint
   const size_t wave_id = (size_t)blockIdx.x * NW + wv, n_waves = (size_t)gridDim.x * NW;
-  const int rows = layout == 0 ? 16 : 32;
+  const int rows = layout == 1 ? 32 : 16;
   const size_t blk_bytes = rows * row_stride, n_blk = footprint / blk_bytes;
-  const size_t lane_off = layout == 0 ? (size_t)(lane >> 2) * row_stride + (lane & 3) * 16
+  const size_t lane_off = layout != 1 ? (size_t)(lane >> 2) * row_stride + (lane & 3) * 16
                                       : (size_t)(lane & 31) * row_stride + (lane >> 5) * 16;
-  const size_t kstep = layout == 0 ? 64 : 32;
+  const size_t kstep = layout == 0 ? 64 : (layout == 1 ? 32 : 128);
   size_t k = 0, blk = wave_id % n_blk;
   const char* p = src + blk * blk_bytes + lane_off;
   auto advance = [&]() {
@@ -477,6 +480,10 @@ extern "C" int moe_prism_microbench(int32_t max_results, moe_prism_microbench_re
   for (int f = 0; f < 3 && ok; ++f) {
     ok = run_stream<16, 8, true>(b, ncu, fps[f], 0, &v, &mhz);
     __builtin_snprintf(nm, sizeof(nm), "global_to_lds_dwordx4_%s", fpn[f]);
+    put(nm, v, "TB/s", mhz);
+    if (!ok) break;
+    ok = run_stream<16, 8, true>(b, ncu, fps[f], 2, &v, &mhz);
+    __builtin_snprintf(nm, sizeof(nm), "global_to_lds_dwordx4_first_half_of_each_line_%s", fpn[f]);
     put(nm, v, "TB/s", mhz);
     if (!ok) break;
     ok = run_stream<8, 8, false>(b, ncu, fps[f], 0, &v, &mhz);

@@ -86,8 +86,9 @@ def test_timing_select_brackets_only_the_named_kernels():
         B.moe_prism_timing_select(None)
         layer()
         t = B.moe_prism_timing_read()
-        # c4 (Is = 704) runs the two-kernel FFN: neither the proxy stage nor the fused kernel is launched
-        idle = ("proxy_select", "ffn_fused")
+        # c4 (Is = 704) runs the two-kernel FFN: neither the proxy stage nor the fused kernel (or
+        # its traffic probe) is launched
+        idle = ("proxy_select", "ffn_fused", "ffn_traffic")
         assert all(v[1] == 1 for k, v in t.items() if k not in idle) and all(t[k][1] == 0 for k in idle)
     finally:
         B.moe_prism_timing_select(None)

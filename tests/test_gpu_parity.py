@@ -106,6 +106,31 @@ def test_narrow_sub_experts_both_ffn_paths(case, path, monkeypatch):
         ((1, 0, 0) if path == "fused" else (0, 1, 1))
 
 
+@pytest.mark.parametrize("stage_k", ["64", "32"])
+@pytest.mark.parametrize("case", [
+    dict(T=900, d=512, N=3, S=2, Is=256, k_max=4),      # both GEMMs in 64-element stages, 256-wide tiles
+    dict(T=1500, d=256, N=5, S=2, Is=320, k_max=6),     # shortest K the 64-element driver takes (4 stages)
+    dict(T=700, d=1024, N=4, S=2, Is=704, k_max=5),     # 192-wide gate-up tiles (1408 rows), 11 down stages
+    dict(T=1100, d=448, N=3, S=4, Is=352, k_max=7),     # Is % 64 != 0: the down GEMM keeps 32-element stages
+    dict(T=5, d=320, N=2, S=1, Is=512, k_max=2),        # a handful of rows: most waves multiply nothing
+    dict(T=2600, d=384, N=2, S=1, Is=1024, k_max=2),    # groups of many m-tiles, several items per workgroup
+])
+def test_wide_sub_experts_both_stage_widths(case, stage_k, monkeypatch):
+    # MOE_PRISM_FFN_K=32 sends the same shapes through the drivers with 32-element K stages
+    monkeypatch.setenv("MOE_PRISM_FFN_K", stage_k)
+    rng = np.random.default_rng(case["T"] + 1)
+    k = rng.integers(0, case["k_max"] + 1, size=case["T"]).astype(np.int32)
+    wl = W.make_workload("wide", dtype="bf16", d=case["d"], n_experts=case["N"], n_sub=case["S"],
+                         inter_sub=case["Is"], req_tokens=[1] * case["T"], req_k=k,
+                         k_max=case["k_max"], seed=case["T"], bias_std=1.0, w_std=0.05)
+    r = run_stages(wl)
+    ref = O.layer_of(wl, return_all=True)
+    check_against_oracle(wl, r, ref)
+    assert row_rel(r["y"], ref["y"]) <= 4e-2 and row_rel(r["out"], ref["out"]) <= 4e-2
+    out, _, _ = run_layer(wl, r["dev"], r["ws"])
+    assert np.array_equal(to_np(out), r["out"])
+
+
 def test_traffic_probe_runs_beside_the_ffn_and_leaves_it_alone():
     # the measurement entry point walks the same tile table with the products left out: it
     # must stay inside y's rows [0, P) (guard rows and the rows >= P keep their fill), refuse
