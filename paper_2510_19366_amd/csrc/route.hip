@@ -365,12 +365,32 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 constexpr int TOPK_WAVES = 4;
 
+// The picks run on integer keys: key(f) = bits ^ ((bits >> 31) & 0x7fffffff) orders like f for
+// every non-NaN binary32 once -0.0 has been replaced by +0.0 (the two compare equal, and equal
+// logits go to the lower id), integer max/min fuse with the cross-lane moves, and INT_MIN, which
+// is the key of no logit (-inf maps to 0x807fffff), marks "taken or absent" without a mask.
+__device__ __forceinline__ int topk_key(float f) {
+  int b = __float_as_int(f);
+  b = b == (int)0x80000000 ? 0 : b;  // -0.0 -> +0.0
+  return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float topk_unkey(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+__device__ __forceinline__ int wave_max_i(int v) {
+  v = max(v, dpp_i<DPP_XOR1>(v));
+  v = max(v, dpp_i<DPP_XOR2>(v));
+  v = max(v, dpp_i<DPP_HALF_MIRROR>(v));
+  v = max(v, dpp_i<DPP_MIRROR>(v));
+  const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+  const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+  return max(max(r0, r1), max(r2, r3));
+}
+
 template <int ELEMS>
 __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
     const float* __restrict__ logits, const int32_t* __restrict__ k_tok, int32_t* __restrict__ ids,
     float* __restrict__ wout, int32_t* __restrict__ hdr, int T, int E, int k_max, int renorm,
     float scale) {
-  extern __shared__ float smem[];  // per wave: k_max exponentials, then k_max ids
+  extern __shared__ float smem[];  // per wave: the k_max picked logits, then their k_max ids
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int t = blockIdx.x * TOPK_WAVES + wv;
   if (t >= T) return;
@@ -384,7 +404,7 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
   }
 
   const float NEG_INF = -__builtin_inff();
-  unsigned long long taken = 0ull;  // bit i: this lane's element i was picked
+  constexpr int GONE = (int)0x80000000;  // key of an element that is taken or beyond E
   float v[ELEMS];
   const float* row = logits + (size_t)t * E;
 #pragma unroll
@@ -405,44 +425,47 @@ __global__ __launch_bounds__(64 * TOPK_WAVES) void topk_kernel(
     denom = wave_sum(denom);
   }
 
-  // Pick j: the wave-wide maximum of the lanes' best free logits, and among the lanes that
-  // hold it the smallest sub-expert id (equal logits, +0.0 == -0.0 included, go to the
-  // lower id).  g = 64 i + lane, so the winner's lane is g & 63.  Only that lane rescans.
-  const int NONE = 0x7fffffff;
-  float bv = NEG_INF;  // this lane's best free logit and its id
-  int bg = NONE;
+  // Pick j: the wave-wide maximum of the lanes' best free keys, and among the lanes that hold
+  // it the smallest sub-expert id (equal logits, +0.0 == -0.0 included, go to the lower id).
+  // g = 64 i + lane, so inside a lane the lower element index is the lower id and the winner's
+  // lane is g & 63.  Only that lane retires its element and rescans.
+  int key[ELEMS];
 #pragma unroll
-  for (int i = 0; i < ELEMS; ++i) {
-    const int g = i * 64 + lane;
-    if (g < E && (bg == NONE || v[i] > bv)) {  // ascending g: strict > keeps the lower id
-      bv = v[i];
-      bg = g;
-    }
-  }
-  float dsel = 0.0f;
+  for (int i = 0; i < ELEMS; ++i) key[i] = i * 64 + lane < E ? topk_key(v[i]) : GONE;
+  const int NONE = 0x7fffffff;
+  int bk, bg;  // this lane's best free key and its id
+  auto rescan = [&]() {
+    bk = GONE;
+#pragma unroll
+    for (int i = 0; i < ELEMS; ++i) bk = max(bk, key[i]);
+    int bi = 0;
+#pragma unroll
+    for (int i = ELEMS - 1; i >= 0; --i) bi = key[i] == bk ? i : bi;  // descending: the lowest index stays
+    bg = bk == GONE ? NONE : bi * 64 + lane;
+  };
+  rescan();
   for (int j = 0; j < kt; ++j) {
-    const float top = wave_max_f(bg == NONE ? NEG_INF : bv);
-    const int g = wave_min_i((bg != NONE && bv == top) ? bg : NONE);
+    const int top = wave_max_i(bk);  // > GONE: k_t <= k_max <= E, a free element is left
+    const unsigned long long holders = __ballot(bk == top);
+    int g;
+    if (__popcll(holders) == 1)  // the usual case: one lane holds the maximum
+      g = __builtin_amdgcn_readlane(bg, __ffsll((long long)holders) - 1);
+    else
+      g = wave_min_i(bk == top ? bg : NONE);
     if (lane == 0) {
-      se[j] = top;  // exponentials are taken for all picks at once after the loop
+      se[j] = topk_unkey(top);  // exponentials are taken for all picks at once after the loop
       sid[j] = g;
     }
-    if ((g & 63) == lane) {  // the winner retires its element and rescans its own logits
-      taken |= 1ull << (g >> 6);
-      bv = NEG_INF;
-      bg = NONE;
+    if ((g & 63) == lane) {
+      const int gi = g >> 6;
 #pragma unroll
-      for (int i = 0; i < ELEMS; ++i) {
-        const int gi = i * 64 + lane;
-        if (gi < E && !((taken >> i) & 1ull) && (bg == NONE || v[i] > bv)) {
-          bv = v[i];
-          bg = gi;
-        }
-      }
+      for (int i = 0; i < ELEMS; ++i) key[i] = i == gi ? GONE : key[i];
+      rescan();
     }
   }
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS writes of lane 0 are done
+  float dsel = 0.0f;
   for (int j = lane; j < kt; j += 64) dsel += expf(se[j] - mx);
   if (renorm) denom = wave_sum(dsel);
   for (int j = lane; j < k_max; j += 64) {
