@@ -149,9 +149,10 @@ static int do_dispatch(const moe_prism_shape* s, const Layout& L, const int32_t*
   int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
   int32_t* chunk = reinterpret_cast<int32_t*>(ws + L.chunk_cnt);
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_COUNT, launch_dispatch_count(ids, chunk, s->T, E, s->k_max, st));
-  MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, cnt, off, hdr, s->T, E, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, cnt, s->T, E, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_PLACE,
-            launch_dispatch_place(ids, chunk, off, sorted_pair, slot_of_pair, s->T, E, s->k_max, st));
+            launch_dispatch_place(ids, chunk, cnt, off, hdr, sorted_pair, slot_of_pair, s->T, E,
+                                  s->k_max, st));
   return MOE_PRISM_OK;
 }
 
@@ -248,9 +249,9 @@ static int do_route_proxy(const moe_prism_shape* s, const Layout& L, const void*
   MP_LAUNCH(MOE_PRISM_K_TOPK, launch_topk(logits0, nullptr, q.ids0, q.w0, hdr, s->T, N, m,
                                           s->renormalize, s->routed_scale, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_COUNT, launch_dispatch_count(q.ids0, chunk, s->T, N, m, st));
-  MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, q.cnt0, q.off0, hdr, s->T, N, st));
+  MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, q.cnt0, s->T, N, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_PLACE,
-            launch_dispatch_place(q.ids0, chunk, q.off0, q.sp0, q.sl0, s->T, N, m, st));
+            launch_dispatch_place(q.ids0, chunk, q.cnt0, q.off0, hdr, q.sp0, q.sl0, s->T, N, m, st));
   MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(q.off0, tiles, hdr, N, L.max_mtiles, s->T * m, st));
   if (s->T == 0) return MOE_PRISM_OK;
   MP_LAUNCH(MOE_PRISM_K_FFN_GATE_UP,

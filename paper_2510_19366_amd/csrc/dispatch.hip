@@ -56,75 +56,112 @@ __global__ __launch_bounds__(256) void dispatch_count_kernel(const int32_t* __re
   }
 }
 
-// One block.  chunk_cnt[c,g] -> exclusive prefix over chunks (in place), cnt[g],
-// off[g] (exclusive prefix over g), off[E] = P.
-constexpr int SCAN_THREADS = 1024;
+// chunk_cnt[c,g] -> exclusive prefix over chunks (in place) and cnt[g].  The chain over chunks
+// is independent per group and moves n_chunks * E * 8 bytes, too much for one CU: a workgroup
+// takes SCAN_GROUPS consecutive groups and cuts the chunk range into SCAN_PARTS pieces that run
+// side by side (a thread sums its piece, the pieces' sums meet in LDS, a second walk over the
+// piece writes the running prefixes).  The prefix over groups (off[]) is left to the place
+// kernel, where every workgroup recomputes it in LDS from cnt[].
+constexpr int SCAN_GROUPS = 16, SCAN_PARTS = 16, SCAN_THREADS = SCAN_GROUPS * SCAN_PARTS;
 __global__ __launch_bounds__(SCAN_THREADS) void dispatch_scan_kernel(int32_t* __restrict__ chunk_cnt,
                                                                      int32_t* __restrict__ cnt,
-                                                                     int32_t* __restrict__ off,
-                                                                     int32_t* __restrict__ hdr,
                                                                      int n_chunks, int E) {
-  __shared__ int32_t wave_tot[SCAN_THREADS / 64];
-  __shared__ int32_t carry;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  if (tid == 0) carry = 0;
-  __syncthreads();
-  for (int g0 = 0; g0 < E; g0 += SCAN_THREADS) {
-    int g = g0 + tid;
-    int run = 0;
-    if (g < E) {
-      constexpr int U = 8;  // loads in flight per thread: the chain over chunks is latency bound
-      int c = 0;
-      for (; c + U <= n_chunks; c += U) {
-        int v[U];
+  __shared__ int32_t part_tot[SCAN_PARTS][SCAN_GROUPS];
+  const int gq = threadIdx.x % SCAN_GROUPS, part = threadIdx.x / SCAN_GROUPS;
+  const int g = blockIdx.x * SCAN_GROUPS + gq;
+  const bool in = g < E;
+  const int cp = (n_chunks + SCAN_PARTS - 1) / SCAN_PARTS;
+  const int c_lo = min(part * cp, n_chunks), c_hi = min(c_lo + cp, n_chunks);
+  int sum = 0;
+  if (in) {
+    constexpr int U = 16;
+    int c = c_lo;
+    for (; c + U <= c_hi; c += U) {
+      int v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = chunk_cnt[(size_t)(c + u) * E + g];
+      for (int u = 0; u < U; ++u) v[u] = chunk_cnt[(size_t)(c + u) * E + g];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          chunk_cnt[(size_t)(c + u) * E + g] = run;
-          run += v[u];
-        }
-      }
-      for (; c < n_chunks; ++c) {
-        int v = chunk_cnt[(size_t)c * E + g];
-        chunk_cnt[(size_t)c * E + g] = run;
-        run += v;
-      }
-      cnt[g] = run;
+      for (int u = 0; u < U; ++u) sum += v[u];
     }
-    // block-wide exclusive scan of `run`
-    int incl = run;
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-      int o = __shfl_up(incl, m, 64);
-      if (lane >= m) incl += o;
-    }
-    if (lane == 63) wave_tot[wv] = incl;
-    __syncthreads();
-    int wbase = 0;
-    for (int i = 0; i < wv; ++i) wbase += wave_tot[i];
-    int excl = carry + wbase + incl - run;
-    if (g < E) off[g] = excl;
-    __syncthreads();
-    if (tid == SCAN_THREADS - 1) carry = excl + run;
-    __syncthreads();
+    for (; c < c_hi; ++c) sum += chunk_cnt[(size_t)c * E + g];
   }
-  if (tid == 0) {
-    off[E] = carry;
-    hdr[HDR_PAIRS] = carry;
+  part_tot[part][gq] = sum;
+  __syncthreads();
+  int run = 0, total = 0;
+#pragma unroll
+  for (int p = 0; p < SCAN_PARTS; ++p) {
+    const int s = part_tot[p][gq];
+    run += p < part ? s : 0;
+    total += s;
+  }
+  if (!in) return;
+  if (part == 0) cnt[g] = total;
+  constexpr int U = 8;
+  int c = c_lo;
+  for (; c + U <= c_hi; c += U) {
+    int v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = chunk_cnt[(size_t)(c + u) * E + g];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      chunk_cnt[(size_t)(c + u) * E + g] = run;
+      run += v[u];
+    }
+  }
+  for (; c < c_hi; ++c) {
+    const int v = chunk_cnt[(size_t)c * E + g];
+    chunk_cnt[(size_t)c * E + g] = run;
+    run += v;
   }
 }
 
+// Exclusive prefix of cnt[0..E) into off_lds[0..E] (off_lds[E] = P) by one workgroup of 256
+// threads: a thread sums a run of consecutive groups, the 256 partial sums are scanned with
+// shuffles, the run is walked again.
+__device__ __forceinline__ void group_offsets(const int32_t* __restrict__ cnt, int32_t* off_lds,
+                                              int32_t* wave_tot, int E) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int per = (E + 255) / 256, lo = min(tid * per, E), hi = min(lo + per, E);
+  int mine = 0;
+  for (int g = lo; g < hi; ++g) mine += cnt[g];
+  int incl = mine;
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    int o = __shfl_up(incl, m, 64);
+    if (lane >= m) incl += o;
+  }
+  if (lane == 63) wave_tot[wv] = incl;
+  __syncthreads();
+  int run = incl - mine;
+  for (int i = 0; i < wv; ++i) run += wave_tot[i];
+  for (int g = lo; g < hi; ++g) {
+    off_lds[g] = run;
+    run += cnt[g];
+  }
+  if (tid == 255) off_lds[E] = run;  // lo == hi == E for the threads past the last group
+  __syncthreads();
+}
+
+// Workgroup c places the pairs of chunk c.  Every workgroup derives the group offsets from
+// cnt[] (E additions); workgroup 0 also writes them out: off[0..E] and the pair count.
 __global__ __launch_bounds__(256) void dispatch_place_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ chunk_base,
-    const int32_t* __restrict__ off, int32_t* __restrict__ sorted_pair,
-    int32_t* __restrict__ slot_of_pair, int T, int E, int W, int k_max) {
-  extern __shared__ u64 masks[];
+    const int32_t* __restrict__ cnt, int32_t* __restrict__ off, int32_t* __restrict__ hdr,
+    int32_t* __restrict__ sorted_pair, int32_t* __restrict__ slot_of_pair, int T, int E, int W,
+    int k_max) {
+  extern __shared__ u64 masks[];  // E * W masks, then E + 1 offsets
+  __shared__ int32_t wave_tot[4];
+  int32_t* off_lds = reinterpret_cast<int32_t*>(masks + (size_t)E * W);
   const int c = blockIdx.x, t0 = c * 64 * W;
-  const int ntok = min(64 * W, T - t0);
+  const int ntok = max(min(64 * W, T - t0), 0);
+  group_offsets(cnt, off_lds, wave_tot, E);
+  const int P = off_lds[E];
+  if (c == 0) {
+    for (int g = threadIdx.x; g <= E; g += blockDim.x) off[g] = off_lds[g];
+    if (threadIdx.x == 0) hdr[HDR_PAIRS] = P;
+  }
   build_masks(ids, masks, t0, ntok, E, W, k_max);
   const int n = ntok * k_max;
-  const int P = off[E];
   const size_t pair0 = (size_t)t0 * k_max;
   for (int i = threadIdx.x; i < n; i += blockDim.x) {
     int g = ids[pair0 + i];
@@ -133,7 +170,7 @@ __global__ __launch_bounds__(256) void dispatch_place_kernel(
       int tl = i / k_max, wq = tl >> 6;
       int rank = __popcll(masks[g * W + wq] & ((1ull << (tl & 63)) - 1ull));
       for (int w = 0; w < wq; ++w) rank += __popcll(masks[g * W + w]);
-      slot = off[g] + chunk_base[(size_t)c * E + g] + rank;
+      slot = off_lds[g] + chunk_base[(size_t)c * E + g] + rank;
       sorted_pair[slot] = (int32_t)(pair0 + i);
     }
     slot_of_pair[pair0 + i] = slot;
@@ -150,22 +187,22 @@ hipError_t launch_dispatch_count(const int32_t* ids, int32_t* chunk_cnt, int T, 
   return hipGetLastError();
 }
 
-hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int32_t* off, int32_t* hdr, int T,
-                                int E, hipStream_t s) {
+hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int T, int E, hipStream_t s) {
   int W = dispatch_chunk_words(E, T);
   int nch = cdiv(T, 64 * W);
-  dispatch_scan_kernel<<<1, SCAN_THREADS, 0, s>>>(chunk_cnt, cnt, off, hdr, nch, E);
+  dispatch_scan_kernel<<<cdiv(E, SCAN_GROUPS), SCAN_THREADS, 0, s>>>(chunk_cnt, cnt, nch, E);
   return hipGetLastError();
 }
 
-hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* off,
-                                 int32_t* sorted_pair, int32_t* slot_of_pair, int T, int E,
-                                 int k_max, hipStream_t s) {
-  if (T == 0) return hipSuccess;
+hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* cnt,
+                                 int32_t* off, int32_t* hdr, int32_t* sorted_pair,
+                                 int32_t* slot_of_pair, int T, int E, int k_max, hipStream_t s) {
   int W = dispatch_chunk_words(E, T);
   int nch = cdiv(T, 64 * W);
-  dispatch_place_kernel<<<nch, 256, (size_t)E * W * 8, s>>>(ids, chunk_base, off, sorted_pair,
-                                                             slot_of_pair, T, E, W, k_max);
+  if (nch < 1) nch = 1;  // T == 0: one workgroup still writes the (all-zero) offsets
+  const size_t lds = (size_t)E * W * 8 + ((size_t)E + 1) * 4;
+  dispatch_place_kernel<<<nch, 256, lds, s>>>(ids, chunk_base, cnt, off, hdr, sorted_pair,
+                                              slot_of_pair, T, E, W, k_max);
   return hipGetLastError();
 }
 

@@ -41,11 +41,11 @@ hipError_t launch_proxy_select(int dtype, const void* act, int act_ld, const int
                                const float* w0, const int32_t* slot0, const int32_t* k_tok,
                                const int32_t* kappa, int32_t* ids, float* w, int32_t* hdr, int T,
                                int S, int r, int m, int k_max, hipStream_t s);
-hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int32_t* off, int32_t* hdr, int T,
-                                int E, hipStream_t s);
-hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* off,
-                                 int32_t* sorted_pair, int32_t* slot_of_pair, int T, int E,
-                                 int k_max, hipStream_t s);
+hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int T, int E, hipStream_t s);
+// also writes off[0..E] and hdr[HDR_PAIRS] (from cnt[])
+hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* cnt,
+                                 int32_t* off, int32_t* hdr, int32_t* sorted_pair,
+                                 int32_t* slot_of_pair, int T, int E, int k_max, hipStream_t s);
 
 // grouped FFN
 hipError_t launch_ffn_tiles(const int32_t* off, MTile* tiles, int32_t* hdr, int E, int max_tiles,
