@@ -142,17 +142,20 @@ static int do_route(const moe_prism_shape* s, const Layout& L, const void* x, co
   return MOE_PRISM_OK;
 }
 
+// with_tiles: the place kernel also builds the grouped FFN's m-tile table (the layer entry
+// points, where the FFN follows on the same offsets; do_ffn is then told not to rebuild it)
 static int do_dispatch(const moe_prism_shape* s, const Layout& L, const int32_t* ids, int32_t* cnt,
                        int32_t* off, int32_t* sorted_pair, int32_t* slot_of_pair, char* ws,
-                       hipStream_t st) {
+                       hipStream_t st, bool with_tiles = false) {
   const int E = s->n_experts * s->n_sub;
   int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
   int32_t* chunk = reinterpret_cast<int32_t*>(ws + L.chunk_cnt);
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_COUNT, launch_dispatch_count(ids, chunk, s->T, E, s->k_max, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, cnt, s->T, E, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_PLACE,
-            launch_dispatch_place(ids, chunk, cnt, off, hdr, sorted_pair, slot_of_pair, s->T, E,
-                                  s->k_max, st));
+            launch_dispatch_place(ids, chunk, cnt, off, hdr, sorted_pair, slot_of_pair,
+                                  with_tiles ? reinterpret_cast<MTile*>(ws + L.tiles) : nullptr,
+                                  L.max_mtiles, s->T, E, s->k_max, st));
   return MOE_PRISM_OK;
 }
 
@@ -167,12 +170,13 @@ static bool use_fused_ffn(const moe_prism_shape* s) {
 
 static int do_ffn(const moe_prism_shape* s, const Layout& L, const void* x, const void* w_gu,
                   const void* w_dn, const int32_t* off, const int32_t* sorted_pair, void* y,
-                  char* ws, hipStream_t st, bool traffic_probe = false) {
+                  char* ws, hipStream_t st, bool traffic_probe = false, bool tiles_built = false) {
   const int E = s->n_experts * s->n_sub;
   int32_t* hdr = reinterpret_cast<int32_t*>(ws + L.hdr);
   MTile* tiles = reinterpret_cast<MTile*>(ws + L.tiles);
   void* h = ws + L.h;
-  MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(off, tiles, hdr, E, L.max_mtiles, s->T * s->k_max, st));
+  if (!tiles_built)
+    MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(off, tiles, hdr, E, L.max_mtiles, s->T * s->k_max, st));
   if (s->T == 0) return MOE_PRISM_OK;
   if (traffic_probe) {
     MP_LAUNCH(MOE_PRISM_K_FFN_TRAFFIC,
@@ -251,7 +255,8 @@ static int do_route_proxy(const moe_prism_shape* s, const Layout& L, const void*
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_COUNT, launch_dispatch_count(q.ids0, chunk, s->T, N, m, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_SCAN, launch_dispatch_scan(chunk, q.cnt0, s->T, N, st));
   MP_LAUNCH(MOE_PRISM_K_DISPATCH_PLACE,
-            launch_dispatch_place(q.ids0, chunk, q.cnt0, q.off0, hdr, q.sp0, q.sl0, s->T, N, m, st));
+            launch_dispatch_place(q.ids0, chunk, q.cnt0, q.off0, hdr, q.sp0, q.sl0, nullptr, 0, s->T, N,
+                                  m, st));
   MP_LAUNCH(MOE_PRISM_K_FFN_TILES, launch_ffn_tiles(q.off0, tiles, hdr, N, L.max_mtiles, s->T * m, st));
   if (s->T == 0) return MOE_PRISM_OK;
   MP_LAUNCH(MOE_PRISM_K_FFN_GATE_UP,
@@ -412,9 +417,9 @@ static int layer_on(const moe_prism_shape* shape, const Layout& L, const void* x
   int rc = do_route(shape, L, x, w_router, router_bias, k_tok, ids, w,
                     reinterpret_cast<float*>(w8 + L.logits), w8, st);
   if (rc) return rc;
-  rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st);
+  rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st, true);
   if (rc) return rc;
-  rc = do_ffn(shape, L, x, w_gate_up, w_down, off, sp, y, w8, st);
+  rc = do_ffn(shape, L, x, w_gate_up, w_down, off, sp, y, w8, st, false, true);
   if (rc) return rc;
   if (shape->T == 0) return MOE_PRISM_OK;
   MP_LAUNCH(MOE_PRISM_K_COMBINE, launch_combine(shape->dtype, y, sl, w, k_tok, out, shape->T,
@@ -493,9 +498,9 @@ int moe_prism_layer_proxy(const moe_prism_shape* shape, const void* x, const voi
   rc = do_route_proxy(shape, L, x, w_router0, router_bias0, w_proxy, m, r, rows_half, kappa, k_tok,
                       ids, w, w8, st);
   if (rc) return rc;
-  rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st);
+  rc = do_dispatch(shape, L, ids, cnt, off, sp, sl, w8, st, true);
   if (rc) return rc;
-  rc = do_ffn(shape, L, x, w_gate_up, w_down, off, sp, y, w8, st);
+  rc = do_ffn(shape, L, x, w_gate_up, w_down, off, sp, y, w8, st, false, true);
   if (rc) return rc;
   if (shape->T == 0) return MOE_PRISM_OK;
   MP_LAUNCH(MOE_PRISM_K_COMBINE, launch_combine(shape->dtype, y, sl, w, k_tok, out, shape->T,

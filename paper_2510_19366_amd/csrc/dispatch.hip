@@ -115,50 +115,99 @@ __global__ __launch_bounds__(SCAN_THREADS) void dispatch_scan_kernel(int32_t* __
   }
 }
 
-// Exclusive prefix of cnt[0..E) into off_lds[0..E] (off_lds[E] = P) by one workgroup of 256
-// threads: a thread sums a run of consecutive groups, the 256 partial sums are scanned with
-// shuffles, the run is walked again.
+// Exclusive prefixes over the groups by one workgroup of 256 threads, into LDS: off_lds[0..E]
+// of the row counts cnt[g] (off_lds[E] = P) and first_lds[0..E] of the m-tile counts
+// ceil(cnt[g] / FFN_BM) (first_lds[E] = number of m-tiles).  A thread sums a run of consecutive
+// groups, the 256 partial sums are scanned with shuffles, the run is walked again.
 __device__ __forceinline__ void group_offsets(const int32_t* __restrict__ cnt, int32_t* off_lds,
-                                              int32_t* wave_tot, int E) {
+                                              int32_t* first_lds, int32_t (*wave_tot)[2], int E) {
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int per = (E + 255) / 256, lo = min(tid * per, E), hi = min(lo + per, E);
-  int mine = 0;
-  for (int g = lo; g < hi; ++g) mine += cnt[g];
-  int incl = mine;
+  int mine = 0, mine_t = 0;
+  for (int g = lo; g < hi; ++g) {
+    const int n = cnt[g];
+    mine += n;
+    mine_t += (n + FFN_BM - 1) / FFN_BM;
+  }
+  int incl = mine, incl_t = mine_t;
 #pragma unroll
   for (int m = 1; m < 64; m <<= 1) {
-    int o = __shfl_up(incl, m, 64);
-    if (lane >= m) incl += o;
+    const int o = __shfl_up(incl, m, 64), ot = __shfl_up(incl_t, m, 64);
+    if (lane >= m) {
+      incl += o;
+      incl_t += ot;
+    }
   }
-  if (lane == 63) wave_tot[wv] = incl;
+  if (lane == 63) {
+    wave_tot[wv][0] = incl;
+    wave_tot[wv][1] = incl_t;
+  }
   __syncthreads();
-  int run = incl - mine;
-  for (int i = 0; i < wv; ++i) run += wave_tot[i];
-  for (int g = lo; g < hi; ++g) {
-    off_lds[g] = run;
-    run += cnt[g];
+  int run = incl - mine, run_t = incl_t - mine_t;
+  for (int i = 0; i < wv; ++i) {
+    run += wave_tot[i][0];
+    run_t += wave_tot[i][1];
   }
-  if (tid == 255) off_lds[E] = run;  // lo == hi == E for the threads past the last group
+  for (int g = lo; g < hi; ++g) {
+    const int n = cnt[g];
+    off_lds[g] = run;
+    first_lds[g] = run_t;
+    run += n;
+    run_t += (n + FFN_BM - 1) / FFN_BM;
+  }
+  if (tid == 255) {  // lo == hi == E for the threads past the last group
+    off_lds[E] = run;
+    first_lds[E] = run_t;
+  }
   __syncthreads();
 }
 
 // Workgroup c places the pairs of chunk c.  Every workgroup derives the group offsets from
 // cnt[] (E additions); workgroup 0 also writes them out: off[0..E] and the pair count.
+// With tiles != nullptr the kernel also builds the grouped FFN's m-tile table (the table
+// ffn_tiles_kernel builds from off[]): workgroup c writes the tiles of groups c, c + grid, ...
+// and workgroup 0 the table's header words.
 __global__ __launch_bounds__(256) void dispatch_place_kernel(
     const int32_t* __restrict__ ids, const int32_t* __restrict__ chunk_base,
     const int32_t* __restrict__ cnt, int32_t* __restrict__ off, int32_t* __restrict__ hdr,
-    int32_t* __restrict__ sorted_pair, int32_t* __restrict__ slot_of_pair, int T, int E, int W,
-    int k_max) {
-  extern __shared__ u64 masks[];  // E * W masks, then E + 1 offsets
-  __shared__ int32_t wave_tot[4];
+    int32_t* __restrict__ sorted_pair, int32_t* __restrict__ slot_of_pair,
+    MTile* __restrict__ tiles, int max_tiles, int T, int E, int W, int k_max) {
+  extern __shared__ u64 masks[];  // E * W masks, then E + 1 offsets, then E + 1 first-tile indices
+  __shared__ int32_t wave_tot[4][2];
   int32_t* off_lds = reinterpret_cast<int32_t*>(masks + (size_t)E * W);
+  int32_t* first_lds = off_lds + E + 1;
   const int c = blockIdx.x, t0 = c * 64 * W;
   const int ntok = max(min(64 * W, T - t0), 0);
-  group_offsets(cnt, off_lds, wave_tot, E);
+  group_offsets(cnt, off_lds, first_lds, wave_tot, E);
   const int P = off_lds[E];
   if (c == 0) {
     for (int g = threadIdx.x; g <= E; g += blockDim.x) off[g] = off_lds[g];
-    if (threadIdx.x == 0) hdr[HDR_PAIRS] = P;
+    if (threadIdx.x == 0) {
+      hdr[HDR_PAIRS] = P;
+      if (tiles != nullptr) {
+        hdr[HDR_MTILES] = min(first_lds[E], max_tiles);
+        hdr[HDR_DYN_GATE_UP] = 0;
+        hdr[HDR_DYN_DOWN] = 0;
+        for (int i = 0; i < 8; ++i) hdr[HDR_DYN_FUSED + i] = 0;
+        if (first_lds[E] > max_tiles) atomicOr(&hdr[HDR_FLAGS], 2);  // cannot happen: P <= T * k_max
+      }
+    }
+  }
+  if (tiles != nullptr) {
+    for (int g = c; g < E; g += gridDim.x) {
+      const int lo = off_lds[g], n = off_lds[g + 1] - lo, first = first_lds[g];
+      const int nt = first_lds[g + 1] - first;
+      for (int i = threadIdx.x; i < nt; i += blockDim.x) {
+        MTile t;
+        t.g = g;
+        t.row0 = lo + i * FFN_BM;
+        t.rows = min(FFN_BM, n - i * FFN_BM);
+        t.first = first;
+        t.count = min(nt, max_tiles - first);
+        t.pad[0] = t.pad[1] = t.pad[2] = 0;
+        if (first + i < max_tiles) tiles[first + i] = t;
+      }
+    }
   }
   build_masks(ids, masks, t0, ntok, E, W, k_max);
   const int n = ntok * k_max;
@@ -196,13 +245,14 @@ hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int T, int E, 
 
 hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* cnt,
                                  int32_t* off, int32_t* hdr, int32_t* sorted_pair,
-                                 int32_t* slot_of_pair, int T, int E, int k_max, hipStream_t s) {
+                                 int32_t* slot_of_pair, MTile* tiles, int max_tiles, int T, int E,
+                                 int k_max, hipStream_t s) {
   int W = dispatch_chunk_words(E, T);
   int nch = cdiv(T, 64 * W);
   if (nch < 1) nch = 1;  // T == 0: one workgroup still writes the (all-zero) offsets
-  const size_t lds = (size_t)E * W * 8 + ((size_t)E + 1) * 4;
+  const size_t lds = (size_t)E * W * 8 + 2 * ((size_t)E + 1) * 4;
   dispatch_place_kernel<<<nch, 256, lds, s>>>(ids, chunk_base, cnt, off, hdr, sorted_pair,
-                                              slot_of_pair, T, E, W, k_max);
+                                              slot_of_pair, tiles, max_tiles, T, E, W, k_max);
   return hipGetLastError();
 }
 

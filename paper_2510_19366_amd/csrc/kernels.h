@@ -42,10 +42,13 @@ hipError_t launch_proxy_select(int dtype, const void* act, int act_ld, const int
                                const int32_t* kappa, int32_t* ids, float* w, int32_t* hdr, int T,
                                int S, int r, int m, int k_max, hipStream_t s);
 hipError_t launch_dispatch_scan(int32_t* chunk_cnt, int32_t* cnt, int T, int E, hipStream_t s);
-// also writes off[0..E] and hdr[HDR_PAIRS] (from cnt[])
+// also writes off[0..E] and hdr[HDR_PAIRS] (from cnt[]) and, with tiles != nullptr, the grouped
+// FFN's m-tile table and its header words (what launch_ffn_tiles builds from off[])
+struct MTile;
 hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, const int32_t* cnt,
                                  int32_t* off, int32_t* hdr, int32_t* sorted_pair,
-                                 int32_t* slot_of_pair, int T, int E, int k_max, hipStream_t s);
+                                 int32_t* slot_of_pair, MTile* tiles, int max_tiles, int T, int E,
+                                 int k_max, hipStream_t s);
 
 // grouped FFN
 hipError_t launch_ffn_tiles(const int32_t* off, MTile* tiles, int32_t* hdr, int E, int max_tiles,

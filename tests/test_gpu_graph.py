@@ -87,8 +87,8 @@ def test_timing_select_brackets_only_the_named_kernels():
         layer()
         t = B.moe_prism_timing_read()
         # c4 (Is = 704) runs the two-kernel FFN: neither the proxy stage nor the fused kernel (or
-        # its traffic probe) is launched
-        idle = ("proxy_select", "ffn_fused", "ffn_traffic")
+        # its traffic probe) is launched; in the layer call the place kernel builds the m-tile table
+        idle = ("proxy_select", "ffn_fused", "ffn_traffic", "ffn_tiles")
         assert all(v[1] == 1 for k, v in t.items() if k not in idle) and all(t[k][1] == 0 for k in idle)
     finally:
         B.moe_prism_timing_select(None)
