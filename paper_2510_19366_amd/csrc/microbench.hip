@@ -292,6 +292,25 @@ __global__ __launch_bounds__(256) void write_kernel(uint4* __restrict__ dst, siz
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
 }
 
+// The fused FFN kernel's output pattern: a workgroup of 8 waves owns 256 consecutive rows of
+// `row_bytes` each and walks along them in steps of `seg` bytes per row (a wave: 32 rows,
+// 8 or more lanes per row segment), so consecutive stores of a wave are row_bytes apart; after
+// row_bytes / seg steps it moves on to its next 256 rows.
+__global__ __launch_bounds__(512) void write_tiles_kernel(char* __restrict__ dst, size_t n_rows,
+                                                          int row_bytes, int seg) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lanes_per_row = seg / 16, rows_per_store = 64 / lanes_per_row;
+  const uint4 v = make_uint4(threadIdx.x, 1, 2, 3);
+  for (size_t tile = blockIdx.x; tile * 256 + 256 <= n_rows; tile += gridDim.x) {
+    char* base = dst + (tile * 256 + wv * 32) * (size_t)row_bytes;
+    for (int s = 0; s < row_bytes / seg; ++s)
+      for (int r0 = 0; r0 < 32; r0 += rows_per_store) {
+        const int r = r0 + lane / lanes_per_row;
+        *reinterpret_cast<uint4*>(base + (size_t)r * row_bytes + (size_t)s * seg + (lane % lanes_per_row) * 16) = v;
+      }
+  }
+}
+
 struct Bufs {
   char* big = nullptr;  // 3 GiB source region, 1 GiB destination behind it
   float* out = nullptr;
@@ -531,6 +550,12 @@ extern "C" int moe_prism_microbench(int32_t max_results, moe_prism_microbench_re
     const size_t n = DST_BYTES / 16;
     ok = timed(b, 5, [&] { write_kernel<<<ncu * 8, 256>>>(reinterpret_cast<uint4*>(b.big + SRC_BYTES), n); }, &ms, &mhz);
     put("hbm_write_1GiB", (double)DST_BYTES / (ms * 1e-3) / 1e12, "TB/s", 0.0);
+  }
+  for (int seg = 128; seg <= 1024 && ok; seg *= 2) {
+    const size_t rows = DST_BYTES / 4096;
+    ok = timed(b, 5, [&] { write_tiles_kernel<<<ncu, 512>>>(b.big + SRC_BYTES, rows, 4096, seg); }, &ms, &mhz);
+    __builtin_snprintf(nm, sizeof(nm), "hbm_write_1GiB_tiles_256rows_x_%dB_per_step", seg);
+    put(nm, (double)DST_BYTES / (ms * 1e-3) / 1e12, "TB/s", 0.0);
   }
   teardown(b);
   return ok ? MOE_PRISM_OK : MOE_PRISM_ERR_LAUNCH;
