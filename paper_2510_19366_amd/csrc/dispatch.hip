@@ -6,8 +6,9 @@
 // sub-expert g a bit mask over the chunk's tokens records who picked g (LDS
 // atomic OR: commutative, so the result does not depend on timing).  The
 // chunk's count for g is the mask's popcount, and the rank of token t among the
-// chunk's pickers of g is the popcount of the mask bits below t.  A single
-// block turns the per-chunk counts into per-chunk bases and group offsets.
+// chunk's pickers of g is the popcount of the mask bits below t.  A second
+// kernel turns the per-chunk counts into per-chunk bases and the groups' totals,
+// and the placing kernel derives the group offsets from the totals.
 // Because a token picks a sub-expert at most once, "token ascending" fixes the
 // order inside a group completely.
 #include "kernels.h"

@@ -9,12 +9,15 @@
 // twice the rate of the 16x16x32 form on this chip).  The weight block is the MFMA's first
 // operand and its rows are fed in a permuted order, so that a lane ends up with 8 or 16
 // consecutive output columns of one slot row and stores them as 16-byte words.
-// Main driver (run_items_dma): operand slabs go global -> LDS directly
-// (global_load_lds_dwordx4) through a ring of 4-5 stages of 32 K-elements that runs across
-// item boundaries, with explicit s_waitcnt vmcnt counts and one s_barrier per stage; for
-// long K the two wave groups alternate between multiplying and preparing the next stage.
-// Fallback (run_items, K too short for the ring): 64-wide slabs through registers into a
-// double-buffered, XOR-swizzled LDS tile, one slab ahead of the MFMAs.
+// Drivers, all with operand slabs going global -> LDS directly (global_load_lds_dwordx4),
+// explicit s_waitcnt vmcnt counts and rings that run across item boundaries:
+//   run_items_k64 (K % 64 == 0): stages of 64 K-elements = whole 128-byte cache lines per row
+//     and copy, ring of 2 stages, one s_barrier per stage, all waves in one instruction stream
+//     with the fragment reads pipelined through the MFMAs;
+//   run_items_dma (other K): ring of 4-5 stages of 32 K-elements; for long K the two wave
+//     groups alternate between multiplying and preparing the next stage;
+//   run_items (K too short for a ring): 64-wide slabs through registers into a double-buffered,
+//     XOR-swizzled LDS tile, one slab ahead of the MFMAs.
 // Narrow sub-experts (Is in {64, 128, 192}) take the fused kernel in ffn_fused_bf16.hip
 // instead; these two kernels serve every other shape.
 #include <cstdlib>
