@@ -551,7 +551,7 @@ extern "C" int moe_prism_microbench(int32_t max_results, moe_prism_microbench_re
     ok = timed(b, 5, [&] { write_kernel<<<ncu * 8, 256>>>(reinterpret_cast<uint4*>(b.big + SRC_BYTES), n); }, &ms, &mhz);
     put("hbm_write_1GiB", (double)DST_BYTES / (ms * 1e-3) / 1e12, "TB/s", 0.0);
   }
-  for (int seg = 128; seg <= 1024 && ok; seg *= 2) {
+  for (int seg = 64; seg <= 1024 && ok; seg *= 2) {
     const size_t rows = DST_BYTES / 4096;
     ok = timed(b, 5, [&] { write_tiles_kernel<<<ncu, 512>>>(b.big + SRC_BYTES, rows, 4096, seg); }, &ms, &mhz);
     __builtin_snprintf(nm, sizeof(nm), "hbm_write_1GiB_tiles_256rows_x_%dB_per_step", seg);
