@@ -87,7 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3_fine_128x4",
                     help="c2_mixtral_8x4 | c3_fine_128x4 | c4_decode_64x2 | c5a_s1_k8 | c5b_s4_k32 | "
-                         "c3_paper_k (the c3 layer with the paper's budget generator, Sec. 4.2 Eq. 7)")
+                         "c3_paper_k (the c3 layer with the paper's budget generator, Sec. 4.2 Eq. 7) | "
+                         "t1_olmoe_p | t1_deepseek_p (the paper's other two layer shapes, Table I)")
     ap.add_argument("--tokens", type=int, default=None, help="token count for the c5 sweep")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)

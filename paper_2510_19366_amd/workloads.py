@@ -175,7 +175,7 @@ def make_workload(name: str, *, dtype: str, d: int, n_experts: int, n_sub: int,
 
 
 CONFIG_NAMES = ("c1_tiny_f32", "c2_mixtral_8x4", "c3_fine_128x4", "c4_decode_64x2",
-                "c5a_s1_k8", "c5b_s4_k32", "c3_paper_k")
+                "c5a_s1_k8", "c5b_s4_k32", "c3_paper_k", "t1_olmoe_p", "t1_deepseek_p")
 
 
 def config(name: str, *, T: Optional[int] = None, with_weights: bool = True,
@@ -201,6 +201,16 @@ def config(name: str, *, T: Optional[int] = None, with_weights: bool = True,
         return make_workload(name, dtype="bf16", d=2048, n_experts=128, n_sub=4, inter_sub=192,
                              req_tokens=(64, 256 // scale_down), req_k=req_k, k_max=32,
                              seed=3, bias_std=1.0, with_weights=with_weights)
+    if name in ("t1_olmoe_p", "t1_deepseek_p"):
+        # the layer shapes of the paper's two other refactored models (Table I: 64 -> 256 routed
+        # experts, 8 -> 32 resp. 6 -> 24 activated, intermediate 1024 -> 256 resp. 1408 -> 352;
+        # hidden size 2048), random weights, per-request budgets uniform up to the activated count
+        olmoe = name == "t1_olmoe_p"
+        return make_workload(name, dtype="bf16", d=2048, n_experts=64, n_sub=4,
+                             inter_sub=256 if olmoe else 352, req_tokens=(64, 256 // scale_down),
+                             k_lo=8 if olmoe else 6, k_hi=32 if olmoe else 24,
+                             k_max=32 if olmoe else 24, seed=11 if olmoe else 12,
+                             with_weights=with_weights)
     if name == "c4_decode_64x2":
         return make_workload(name, dtype="bf16", d=2048, n_experts=64, n_sub=2, inter_sub=704,
                              req_tokens=(8192 // scale_down, 1), k_choices=[4, 12], k_max=12,

@@ -79,6 +79,14 @@ def test_c2_mixtral_8x4_full():
     check_full(wl, n_sample=wl.T)
 
 
+@pytest.mark.parametrize("name", ["t1_olmoe_p", "t1_deepseek_p"])
+def test_table1_model_shapes_full(name):
+    # the paper's other two refactored layers (Table I): Is = 256 runs both GEMMs in 64-element K
+    # stages, Is = 352 the gate-up GEMM in 64- and the down GEMM in 32-element stages
+    wl = workload(name)
+    check_full(wl, wl.T)
+
+
 @pytest.mark.parametrize("T", [512, 2048, 16384, 65536])
 def test_c5_matched_budget_split_vs_whole(T):
     # Sec. 3.2.2: repeated-row gate at k = S*k_orig with scale S reproduces the undivided layer
