@@ -148,6 +148,22 @@ __device__ __forceinline__ void dma16(const void* g, uint32_t lds) {
                : "v"(g), "s"(lds)
                : "memory");
 }
+// the same copy with a cache-policy modifier: 1 = sc0, 2 = sc1, 3 = sc0 sc1, 4 = nt
+template <int policy>
+__device__ __forceinline__ void dma16_policy(const void* g, uint32_t lds) {
+  uint32_t keep;
+#define MPUB_DMA(MOD)                                                                                   \
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 1\n\tglobal_load_lds_dwordx4 %1, off" MOD "\n\t" \
+               "s_mov_b32 m0, %0"                                                                       \
+               : "=&s"(keep)                                                                            \
+               : "v"(g), "s"(lds)                                                                       \
+               : "memory")
+  if constexpr (policy == 1) MPUB_DMA(" sc0");
+  else if constexpr (policy == 2) MPUB_DMA(" sc1");
+  else if constexpr (policy == 3) MPUB_DMA(" sc0 sc1");
+  else MPUB_DMA(" nt");
+#undef MPUB_DMA
+}
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -161,7 +177,7 @@ __device__ __forceinline__ void wait_vm() {
 // layout 2: like 0, but a wave steps 128 bytes along the row, so only the first 64 bytes of
 // every 128-byte line are ever requested (what a K stage of 32 bf16 elements asks of the
 // caches when the other half of the line is needed a stage later).
-template <int DEPTH, int NW, bool TO_LDS>
+template <int DEPTH, int NW, bool TO_LDS, int POLICY = 0>
 __global__ __launch_bounds__(NW * 64) void stream_kernel(const char* __restrict__ src,
                                                          size_t footprint, int iters,
                                                          size_t row_stride, int layout, float* out,
@@ -193,7 +209,8 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const char* __restrict_
   const uint64_t c0 = shader_clock(), r0 = real_clock();
   if (TO_LDS) {
     for (int it = 0; it < iters; ++it) {
-      dma16(p + k, base + (it % (DEPTH + 1)) * 1024);
+      if constexpr (POLICY == 0) dma16(p + k, base + (it % (DEPTH + 1)) * 1024);
+      else dma16_policy<POLICY>(p + k, base + (it % (DEPTH + 1)) * 1024);
       advance();
       wait_vm<DEPTH>();
     }
@@ -396,9 +413,9 @@ static bool run_lds_mfma(Bufs& b, int ncu, int variant, double* tflops, double* 
   return true;
 }
 
-template <int DEPTH, int NW, bool TO_LDS>
+template <int DEPTH, int NW, bool TO_LDS, int POLICY = 0>
 static bool run_stream(Bufs& b, int ncu, size_t footprint, int layout, double* tbs, double* mhz) {
-  auto kern = stream_kernel<DEPTH, NW, TO_LDS>;
+  auto kern = stream_kernel<DEPTH, NW, TO_LDS, POLICY>;
   const size_t lds = (size_t)NW * (DEPTH + 1) * 1024;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -504,6 +521,16 @@ extern "C" int moe_prism_microbench(int32_t max_results, moe_prism_microbench_re
     ok = run_stream<16, 8, true>(b, ncu, fps[f], 2, &v, &mhz);
     __builtin_snprintf(nm, sizeof(nm), "global_to_lds_dwordx4_first_half_of_each_line_%s", fpn[f]);
     put(nm, v, "TB/s", mhz);
+    if (!ok) break;
+    const char* pol[5] = {"", "sc0", "sc1", "sc0_sc1", "nt"};
+    for (int q = 1; q <= 4 && ok && f == 0; ++q) {  // cache-policy modifiers, L2-resident footprint
+      if (q == 1) ok = run_stream<16, 8, true, 1>(b, ncu, fps[f], 2, &v, &mhz);
+      if (q == 2) ok = run_stream<16, 8, true, 2>(b, ncu, fps[f], 2, &v, &mhz);
+      if (q == 3) ok = run_stream<16, 8, true, 3>(b, ncu, fps[f], 2, &v, &mhz);
+      if (q == 4) ok = run_stream<16, 8, true, 4>(b, ncu, fps[f], 2, &v, &mhz);
+      __builtin_snprintf(nm, sizeof(nm), "global_to_lds_dwordx4_first_half_of_each_line_%s_%s", pol[q], fpn[f]);
+      put(nm, v, "TB/s", mhz);
+    }
     if (!ok) break;
     ok = run_stream<8, 8, false>(b, ncu, fps[f], 0, &v, &mhz);
     __builtin_snprintf(nm, sizeof(nm), "global_to_regs_dwordx4_rows_of_4_lanes_%s", fpn[f]);
