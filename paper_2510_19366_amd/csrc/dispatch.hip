@@ -252,6 +252,17 @@ hipError_t launch_dispatch_place(const int32_t* ids, const int32_t* chunk_base, 
   int nch = cdiv(T, 64 * W);
   if (nch < 1) nch = 1;  // T == 0: one workgroup still writes the (all-zero) offsets
   const size_t lds = (size_t)E * W * 8 + 2 * ((size_t)E + 1) * 4;
+  // up to 96 KiB + 8 bytes (E = 4096, W = 2): beyond the default limit for dynamic LDS, so the
+  // limit is raised once per device (no other runtime call on the launch path afterwards)
+  static bool raised[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+  if (dev < 0 || !raised[dev]) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(dispatch_place_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 100 * 1024);
+    if (e != hipSuccess) return e;
+    if (dev >= 0) raised[dev] = true;
+  }
   dispatch_place_kernel<<<nch, 256, lds, s>>>(ids, chunk_base, cnt, off, hdr, sorted_pair,
                                               slot_of_pair, tiles, max_tiles, T, E, W, k_max);
   return hipGetLastError();

@@ -250,6 +250,27 @@ def test_largest_supported_router_and_budget():
         assert e.value.code == -2
 
 
+@pytest.mark.parametrize("T,E,k_max", [(33000, 4096, 3),   # two 64-token words per chunk: the largest LDS footprint
+                                       (70000, 1000, 5),   # four words per chunk, E not a multiple of 4
+                                       (1, 7, 7), (257, 33, 2)])
+def test_dispatch_alone_on_synthetic_picks(T, E, k_max):
+    # the dispatch stage by itself on picks that no router produced: distinct ids per token,
+    # -1 padded to a random budget; tables bit for bit
+    rng = np.random.default_rng(T + E)
+    ids = np.full((T, k_max), -1, np.int32)
+    for t in range(T):
+        kt = int(rng.integers(0, k_max + 1))
+        ids[t, :kt] = rng.choice(E, size=kt, replace=False)
+    shape = B.make_shape(T, 64, E, 1, 32, k_max, "bf16")
+    ws = B.alloc_workspace(shape)
+    cnt, off, sp, sl = B.moe_prism_dispatch(shape, torch.from_numpy(ids).cuda(), ws)
+    torch.cuda.synchronize()
+    rc, ro, rsp, rsl = O.dispatch(ids, E)
+    assert np.array_equal(to_np(cnt), rc) and np.array_equal(to_np(off), ro)
+    assert np.array_equal(to_np(sp), rsp) and np.array_equal(to_np(sl), rsl)
+    assert B.moe_prism_status(ws)[1] == int(ro[-1])   # the status word belongs to the route stage
+
+
 def test_everything_routed_to_one_sub_expert():
     # the degenerate load: one group holds all T rows (many m-tiles), every other group is empty
     T = 3000
