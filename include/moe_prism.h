@@ -128,6 +128,11 @@ MOE_PRISM_API int moe_prism_dispatch(const moe_prism_shape* shape, const int32_t
  * w_gate_up [E, 2*Is, d]: rows 0..Is-1 are the gate rows, Is..2Is-1 the up rows of
  * sub-expert g; w_down [E, d, Is].  y [T*k_max, d] in shape->dtype, rows >= P are
  * not written.  bf16: fp32 accumulation, h rounded to bf16 once, y rounded once.
+ * Kernel choice (bf16): sub-experts with Is in {64, 128, 192} (and d >= 256) run one
+ * fused kernel, all other shapes a gate-up and a down kernel.  Two environment
+ * variables, read at every call, exist for A/B measurements and tests:
+ * MOE_PRISM_FFN=split forces the two-kernel path, MOE_PRISM_FFN_K=32 its driver
+ * with 32-element K stages.  Results agree within the rounding stated above.
  */
 MOE_PRISM_API int moe_prism_grouped_ffn(const moe_prism_shape* shape, const void* x, const void* w_gate_up,
                           const void* w_down, const int32_t* group_offset,

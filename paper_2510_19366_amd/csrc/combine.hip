@@ -66,15 +66,21 @@ __global__ __launch_bounds__(256) void combine_kernel(const void* __restrict__ y
   __shared__ int32_t s_slot[CB_CHUNK];
   __shared__ float s_w[CB_CHUNK];
   const int t = blockIdx.x;
+  // The slots and weights of all k_max picks are requested together with the token's budget
+  // (one memory latency instead of two in a row); picks beyond the budget are masked afterwards.
   int kt = k_tok[t];
+  const int kp = (k_max + RU - 1) / RU * RU;  // <= CB_CHUNK
+  for (int j = threadIdx.x; j < kp; j += 256) {
+    const bool in = j < k_max;
+    const int sl = in ? slot_of_pair[(size_t)t * k_max + j] : -1;
+    const float wj = in ? w[(size_t)t * k_max + j] : 0.0f;
+    const int ktc = kt < 0 ? 0 : (kt > k_max ? k_max : kt);
+    const bool ok = j < ktc && sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing:
+    s_slot[j] = ok ? sl : -1;                           // its row is not even read (y may hold anything there)
+    s_w[j] = ok ? wj : 0.0f;
+  }
   kt = kt < 0 ? 0 : (kt > k_max ? k_max : kt);
   const int ktp = (kt + RU - 1) / RU * RU;
-  for (int j = threadIdx.x; j < ktp; j += 256) {
-    const int sl = j < kt ? slot_of_pair[(size_t)t * k_max + j] : -1;
-    const bool ok = sl >= 0 && sl < n_rows;  // a pick without a slot contributes nothing:
-    s_slot[j] = ok ? sl : -1;                // its row is not even read (y may hold anything there)
-    s_w[j] = ok ? w[(size_t)t * k_max + j] : 0.0f;
-  }
   __syncthreads();
   for (int col = threadIdx.x * N; col < d; col += 256 * N) {
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
