@@ -53,6 +53,67 @@ __global__ __launch_bounds__(256) void mfma_reg_kernel(const uint4* __restrict__
   if (blockIdx.x == 0 && threadIdx.x == 0) *clk = Clk{c1 - c0, r1 - r0};
 }
 
+// The rank-1 fp32 form the router-logits kernel issues (one binary32 FMA per output and
+// instruction): NACC independent chains of 32 x 64 outputs per wave.
+typedef __attribute__((__vector_size__(32 * sizeof(float)))) float f32x32;
+template <int NACC>
+__global__ __launch_bounds__(256) void mfma_f32_rank1_kernel(const uint4* __restrict__ data, float* out,
+                                                            int iters, Clk* clk) {
+  const uint4 q = data[threadIdx.x];
+  const float a = __uint_as_float(q.x << 16), b = __uint_as_float(q.y << 16);  // bf16 bits widened
+  f32x32 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int j = 0; j < 32; ++j) acc[i][j] = 0.0f;
+  const uint64_t c0 = shader_clock(), r0 = real_clock();
+  for (int it = 0; it < iters; ++it) {
+    static_assert(NACC == 2, "two chains: A block 0 and A block 1");
+    acc[0] = __builtin_amdgcn_mfma_f32_32x32x1f32(a, b, acc[0], 1, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_32x32x1f32(a, b, acc[1], 1, 1, 0);
+  }
+  const uint64_t c1 = shader_clock(), r1 = real_clock();
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < NACC; ++i)
+#pragma unroll
+    for (int j = 0; j < 32; ++j) s += acc[i][j];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *clk = Clk{c1 - c0, r1 - r0};
+}
+
+// The same with a different pair of operand registers for every k step (32 pairs, as the
+// logits kernel has them after reading a slab from LDS).
+__global__ __launch_bounds__(256) void mfma_f32_rank1_many_operands_kernel(const uint4* __restrict__ data,
+                                                                          float* out, int iters, Clk* clk) {
+  float fa[32], fb[32];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint4 q = data[(threadIdx.x + 37 * i) & 4095], r = data[(threadIdx.x + 53 * i + 11) & 4095];
+    fa[4 * i] = __uint_as_float(q.x << 16); fa[4 * i + 1] = __uint_as_float(q.y << 16);
+    fa[4 * i + 2] = __uint_as_float(q.z << 16); fa[4 * i + 3] = __uint_as_float(q.w << 16);
+    fb[4 * i] = __uint_as_float(r.x << 16); fb[4 * i + 1] = __uint_as_float(r.y << 16);
+    fb[4 * i + 2] = __uint_as_float(r.z << 16); fb[4 * i + 3] = __uint_as_float(r.w << 16);
+  }
+  f32x32 acc0, acc1;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) acc0[j] = acc1[j] = 0.0f;
+  const uint64_t c0 = shader_clock(), r0 = real_clock();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      acc0 = __builtin_amdgcn_mfma_f32_32x32x1f32(fa[i], fb[i], acc0, 1, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x1f32(fa[i], fb[i], acc1, 1, 1, 0);
+    }
+  }
+  const uint64_t c1 = shader_clock(), r1 = real_clock();
+  float s = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 32; ++j) s += acc0[j] + acc1[j];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *clk = Clk{c1 - c0, r1 - r0};
+}
+
 // ------------------------------------------------------------------ matrix cores fed from LDS
 // A workgroup of WAVES waves multiplies a resident LDS tile again and again: rows of 32
 // K-elements (64 bytes, 4 chunks of 16 bytes, XOR-swizzled like the FFN kernels' ring
@@ -474,6 +535,23 @@ extern "C" int moe_prism_microbench(int32_t max_results, moe_prism_microbench_re
     ok = timed(b, 3, [&] { mfma_reg_kernel<4><<<2 * grid, 256>>>(b.data[var], b.out, iters, b.clk); }, &ms, &mhz);
     v = 2.0 * 32 * 32 * 16 * 4 * (double)iters * grid * 8 / (ms * 1e-3) / 1e12;
     __builtin_snprintf(nm, sizeof(nm), "mfma_32x32x16_bf16_registers_%s_2waves_per_simd", dname[var]);
+    put(nm, v, "TFLOP/s", mhz);
+  }
+  // 1b. the rank-1 fp32 form of the logits kernel: two chains per wave, two waves per SIMD
+  for (int var = 0; var < 2 && ok; ++var) {
+    const int iters = 20000, grid = 2 * ncu;
+    ok = timed(b, 3, [&] { mfma_f32_rank1_kernel<2><<<grid, 256>>>(b.data[var], b.out, iters, b.clk); }, &ms, &mhz);
+    v = 2.0 * 32 * 64 * 2 * (double)iters * grid * 4 / (ms * 1e-3) / 1e12;
+    __builtin_snprintf(nm, sizeof(nm), "mfma_32x32x1_2b_f32_registers_%s_2waves_per_simd", dname[var]);
+    put(nm, v, "TFLOP/s", mhz);
+  }
+  // long run (about 2 ms) and a run as short as the logits kernel at 16K tokens x 512 sub-experts
+  for (int var = 0; var < 4 && ok; ++var) {
+    const int iters = var < 2 ? 640 : 64, grid = 2 * ncu;
+    ok = timed(b, 3, [&] { mfma_f32_rank1_many_operands_kernel<<<grid, 256>>>(b.data[var & 1], b.out, iters, b.clk); }, &ms, &mhz);
+    v = 2.0 * 32 * 64 * 64 * (double)iters * grid * 4 / (ms * 1e-3) / 1e12;
+    __builtin_snprintf(nm, sizeof(nm), "mfma_32x32x1_2b_f32_32_operand_pairs_%s_2waves_per_simd%s", dname[var & 1],
+                       var < 2 ? "" : "_0.2ms_run");
     put(nm, v, "TFLOP/s", mhz);
   }
   // 2. LDS-fed MFMA, wave tiles of the FFN kernels and larger ones
