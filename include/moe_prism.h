@@ -151,6 +151,11 @@ MOE_PRISM_API int moe_prism_combine(const moe_prism_shape* shape, const void* y,
 /*
  * The whole path route -> dispatch -> grouped FFN -> combine on one stream with
  * no host synchronisation; all intermediates live in ws.  out [T,d].
+ * Stream capture: the first call of a kernel on a device raises that kernel's
+ * dynamic-LDS limit (a runtime call that must not be recorded), so call the entry
+ * point once eagerly on the device before capturing it into a HIP graph; afterwards
+ * a call only launches kernels, and one captured graph serves any budget mix of the
+ * same shape (sizes are read from device memory).
  */
 MOE_PRISM_API int moe_prism_layer(const moe_prism_shape* shape, const void* x, const void* w_router,
                     const float* router_bias, const int32_t* k_tok, const void* w_gate_up,
